@@ -1,0 +1,198 @@
+/*
+ * C-ABI of the MI355X hot path of one HSTU serving step over a single shared
+ * HBM page pool (embedding hot cache + paged KV cache behind one movable
+ * EMB:KV boundary).
+ *
+ * Conventions
+ *   - plain C, opaque handles, every call returns int32_t:
+ *       0 = OK, > 0 = OK with a condition (RACER_DEFERRED, RACER_NOT_FOUND),
+ *       < 0 = error (negated errno-style codes below); nothing is thrown.
+ *   - "dev" pointers are device addresses, "host" pointers are host addresses.
+ *     All data buffers (the pool's backing store, ids, outputs, page tables,
+ *     weights) are owned by the caller; the library allocates only its own
+ *     metadata and workspaces and frees them in the destroy calls.  It never
+ *     frees or reallocates caller memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Work
+ *     is enqueued on it and the call returns without waiting unless stated.
+ *     All calls on one pool must be issued from one host thread at a time and
+ *     on streams the caller keeps ordered with one another; two calls that
+ *     overlap on one pool race.
+ *   - Counters live on the device; pool_stats() waits for the pool's last
+ *     stream before reading them.
+ */
+#ifndef RACER_POOL_H
+#define RACER_POOL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RACER_OK 0
+#define RACER_DEFERRED 1  /* EMB expansion only partly served (paper Sec. IV-B: "throttled/deferred") */
+#define RACER_NOT_FOUND 2 /* kv_seq_*: no such resident sequence */
+#define RACER_EINVAL (-22)
+#define RACER_ENOMEM (-12)
+#define RACER_ERANGE (-34)
+#define RACER_EBUSY (-16)
+#define RACER_EHIP (-5) /* a HIP runtime call failed; see racer_last_error() */
+
+#define RACER_ELEM_F32 0
+#define RACER_ELEM_BF16 1
+#define RACER_TAG_EMPTY 0xFFFFFFFFu
+
+typedef struct racer_pool racer_pool_t;
+typedef struct racer_hstu racer_hstu_t;
+
+typedef struct {
+  uint32_t row_bytes;     /* R: bytes of one embedding row = d * elem size; multiple of 16 */
+  uint32_t elem;          /* RACER_ELEM_F32 or RACER_ELEM_BF16 */
+  uint32_t page_tokens;   /* KV tokens per page */
+  uint32_t w_max;         /* ways per set when the whole pool is EMB: power of two <= 32 */
+  const void* host_table; /* host: pinned, device-mapped table [rows][row_bytes]; may be NULL if emb_lookup is unused */
+  uint64_t rows;          /* rows of host_table, < 2^32 - 1 */
+  double emb_frac0;       /* initial EMB fraction in [0, 1] */
+} racer_pool_cfg;
+
+typedef struct {
+  uint64_t lookups, hits, misses, unique_misses, inserted, evicted, bypassed, invalid_ids;
+  uint64_t shrink_evicted, shrink_moved;
+  uint64_t pages_total, pages_emb, pages_kv_used, pages_kv_free;
+  uint64_t seqs_resident, seqs_evicted;
+  uint64_t batch;        /* number of emb_lookup calls so far (the LRU clock) */
+  uint64_t bad_pages;    /* page-table entries outside the pool seen by hstu kernels (skipped) */
+} racer_pool_stats;
+
+/* ---- pool (paper Sec. IV-B: one shared paged HBM space, movable logical EMB:KV boundary;
+ *      Sec. IV-A: M_emb = alpha * M, M_kv = (1 - alpha) * M) -------------------------------
+ *
+ * pool_create: dev_base (dev, caller-owned, 256-byte aligned) backs bytes/page_size pages.
+ * Requirements: bytes % page_size == 0, page_size % row_bytes == 0, pages % w_max == 0,
+ * pages < 2^31.  Page p occupies [dev_base + p*page_size, +page_size).  On the KV side a
+ * page holds page_tokens tokens of all layers ([layer][K|V][head][token][d_h]); on the EMB
+ * side it holds page_size/row_bytes embedding slots.  round-half-away(emb_frac0 * pages)
+ * lowest-numbered pages start on the EMB side, the rest on the KV free list.
+ * dev_base == NULL creates a metadata-only pool (host bookkeeping works, device calls
+ * return RACER_EINVAL): this is what CPU-only hosts can exercise.
+ * Errors: RACER_EINVAL (geometry), RACER_ENOMEM / RACER_EHIP (metadata allocation). */
+int32_t pool_create(void* dev_base, uint64_t bytes, uint64_t page_size, const racer_pool_cfg* cfg,
+                    racer_pool_t** out);
+int32_t pool_destroy(racer_pool_t* pool);
+
+/* pool_set_split (paper Sec. IV-B "Embedding-only boundary adjustment", Eq. 6 for the
+ * domain): move the boundary to round(emb_frac * pages).  emb_frac outside [0.1, 0.9] ->
+ * RACER_EINVAL.  Growing EMB: free KV pages are taken lowest id first; if too few are
+ * free, cold unpinned sequences are dropped in LRU order (metadata only); if still short
+ * the pages that exist are taken and RACER_DEFERRED is returned with *achieved < emb_frac.
+ * Shrinking EMB: per cache set the least recently used entries leave, survivors from the
+ * removed ways move into vacated lower ways (device-to-device, enqueued on `stream`), the
+ * tail pages return to the KV free list.  Resident KV pages never move and no host<->device
+ * data copy is made.  Host metadata is final on return; `achieved` (host, may be NULL)
+ * receives pages_emb / pages. */
+int32_t pool_set_split(racer_pool_t* pool, double emb_frac, void* stream, double* achieved);
+
+/* pool_stats: waits for the pool's last stream, then fills *out (host). */
+int32_t pool_stats(racer_pool_t* pool, racer_pool_stats* out);
+
+/* pool_dump / emb_cache_dump: parity helpers. Host output arrays, NULL = skip.
+ * emb_pages[pages_emb] logical->physical, owner[pages] (0 free, 1 EMB, 2 KV);
+ * tags, stamps: [sets][w_max] copied from the device after a stream wait. */
+int32_t pool_dump(racer_pool_t* pool, int64_t* emb_pages, uint8_t* owner);
+int32_t emb_cache_dump(racer_pool_t* pool, uint32_t* tags, uint32_t* stamps);
+uint64_t pool_num_sets(const racer_pool_t* pool);
+/* physical slot (page * slots_per_page + offset) of way `way` of set `set`, -1 if absent */
+int64_t pool_slot_of(const racer_pool_t* pool, uint64_t set, uint32_t way);
+
+/* ---- KV sequences (paper Sec. IV-B: paged block pool with free list and page tables,
+ *      indexed per user; LRU reclaim of cold blocks is metadata-only; in-flight blocks
+ *      are pinned).  Host-only calls, no device work. --------------------------------------
+ * kv_seq_reserve: make sequence `key` cover at least `tokens` tokens (never shrinks).  New
+ * pages are the lowest-numbered free ones; when none are free, other unpinned sequences
+ * are dropped least-recently-used first.  If free + reclaimable pages do not suffice:
+ * RACER_ENOMEM and no state change.  Touches the sequence's LRU stamp.  pages_out (host,
+ * may be NULL) receives all pages of the sequence if cap suffices, else RACER_EINVAL. */
+int32_t kv_seq_reserve(racer_pool_t* pool, uint64_t key, uint32_t tokens, int32_t* pages_out,
+                       uint32_t cap, uint32_t* n_pages_out);
+int32_t kv_seq_lookup(const racer_pool_t* pool, uint64_t key, uint32_t* tokens, int32_t* pages_out,
+                      uint32_t cap, uint32_t* n_pages_out);
+int32_t kv_seq_pin(racer_pool_t* pool, uint64_t key);   /* also touches the LRU stamp */
+int32_t kv_seq_unpin(racer_pool_t* pool, uint64_t key);
+int32_t kv_seq_release(racer_pool_t* pool, uint64_t key); /* RACER_EBUSY while pinned */
+
+/* ---- emb_lookup (paper Sec. II-B stage "EMB lookup": probe the node's HBM embedding
+ *      cache, fetch absent rows from the CPU-resident table; Sec. IV-B: LRU-managed slab
+ *      with page-granular allocation) -------------------------------------------------------
+ * ids (dev) int64[n]; bag = lookups summed per output row (n % bag == 0); out (dev)
+ * [n/bag][row_bytes] in the pool's element type; hit_flags (dev, may be NULL) u8[n].
+ * One call is one LRU batch: hit = resident when the call starts; every hit way is stamped
+ * with the batch number; each distinct missing id is inserted once, in order of first
+ * occurrence (empty way, else least recently used way not touched in this batch, else the
+ * id bypasses the cache).  out rows always equal the host table's rows; bags are summed in
+ * fp32 left to right and rounded once.  ids outside [0, rows) count as invalid_ids and
+ * contribute zeros.  Errors: RACER_EINVAL (bag, NULL pool data), RACER_EHIP. */
+int32_t emb_lookup(racer_pool_t* pool, const int64_t* ids, uint64_t n, uint32_t bag, void* out,
+                   uint8_t* hit_flags, void* stream);
+
+/* ---- HSTU (paper Sec. II-A/II-B stage "Compute": stacked HSTU blocks that reuse resident
+ *      KV state; equations are the published HSTU layer) ------------------------------------ */
+typedef struct {
+  uint32_t L, d, H;
+  uint32_t elem;        /* storage type of activations, W1/W2 and KV: RACER_ELEM_* */
+  uint32_t page_tokens; /* must equal the pool's */
+  uint32_t n_pos;       /* rows of the positional bias table; distance is clamped to n_pos-1 */
+  uint32_t n_time;      /* log2 time-gap buckets, clamped to n_time-1 */
+  float n_scale;        /* attention output is divided by this */
+  float eps;            /* LayerNorm epsilon */
+} racer_hstu_cfg;
+
+/* device pointers, all layers concatenated; w1 [L][d][4d] and w2 [L][d][d] in the model's
+ * element type (row-major, input-major: y = x W), everything else fp32:
+ * ln1_g, ln1_b [L][d]; b1 [L][4d]; ln2_g, ln2_b [L][d]; b2 [L][d]; pos [L][H][n_pos];
+ * time [L][H][n_time].  Columns of W1 are ordered U | V | Q | K, head h owning columns
+ * h*d/H .. (h+1)*d/H - 1 of each block.  The arrays must stay valid while the model lives. */
+typedef struct {
+  const void *ln1_g, *ln1_b, *w1, *b1, *ln2_g, *ln2_b, *w2, *b2, *pos, *time;
+} racer_hstu_weights;
+
+typedef struct {
+  uint32_t prefix_len;     /* tokens whose K,V already sit in the request's pages */
+  uint32_t new_len;        /* tokens processed by this step */
+  uint64_t page_table_off; /* first entry of this request in kv_page_tables */
+  uint64_t ts_off;         /* first of prefix_len + new_len timestamps in ts */
+  uint64_t x_off;          /* first of new_len rows in x_in / out */
+} racer_hstu_req;
+
+/* Supported shapes: elem bf16 with d/H == 64 (MFMA path) or elem fp32 with d/H <= 64;
+ * d % 64 == 0 for bf16, d % 16 == 0 for fp32; otherwise RACER_EINVAL. */
+int32_t hstu_model_create(const racer_hstu_cfg* cfg, const racer_hstu_weights* weights,
+                          racer_hstu_t** out);
+int32_t hstu_model_destroy(racer_hstu_t* model);
+
+/* hstu_step: all L layers for B requests.  reqs (host) [B]; kv_page_tables (dev) int32,
+ * n_page_entries long, request r using ceil((prefix+new)/page_tokens) entries from its
+ * offset; x_in (dev) [N][d] new-token inputs (N = sum new_len); ts (dev) int64 seconds,
+ * non-decreasing per request; out (dev) [N][d].  For every layer the new tokens' K,V are
+ * written into the request's pages at positions prefix_len.., then every new token attends
+ * to positions 0..its own through the page table.  Page ids outside the pool are skipped
+ * and counted in bad_pages.  Errors: RACER_EINVAL (shape mismatch with the pool, offsets
+ * beyond n_page_entries), RACER_ENOMEM/RACER_EHIP (workspace). */
+int32_t hstu_step(racer_pool_t* pool, racer_hstu_t* model, const racer_hstu_req* reqs, uint32_t B,
+                  const int32_t* kv_page_tables, uint64_t n_page_entries, const void* x_in,
+                  const int64_t* ts, void* out, void* stream);
+
+/* hstu_attn_paged: the attention of one layer alone (for kernel-level measurement and
+ * parity): q (dev) [N][d] in the element type, K,V read from the pages as they are,
+ * o (dev) [N][d] = (1/n) sum_{j<=p} SiLU(q.k_j + rab(p, j)) v_j per head. */
+int32_t hstu_attn_paged(racer_pool_t* pool, racer_hstu_t* model, uint32_t layer,
+                        const racer_hstu_req* reqs, uint32_t B, const int32_t* kv_page_tables,
+                        uint64_t n_page_entries, const void* q, const int64_t* ts, void* o,
+                        void* stream);
+
+/* text of the last HIP error seen by this library on the calling thread ("" if none) */
+const char* racer_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,553 @@
+// Embedding hot-cache kernels for gfx950: wavefront-parallel set probe fused with the
+// row gather, and the miss path (LDS-staged compaction, dedupe by first occurrence,
+// ordered per-set victim choice, zero-copy fetch from the pinned host table).
+//
+// The policy these kernels realise (paper Sec. IV-B: an LRU-managed EMB slab with
+// page-granular allocation; the batch rules are this build's reading):
+//   hit = resident when the batch starts; hit ways are stamped with the batch number;
+//   each distinct missing id is inserted once, in first-occurrence order, into the
+//   lowest empty way of its set, else into the way with the least (stamp, way) whose
+//   stamp is older than this batch, else it bypasses the cache.
+// Because a set's victim candidates are fixed once the probe has stamped the hits, the
+// k-th unique miss of a set (by first occurrence) simply takes the k-th candidate, so
+// the insertion order needs no serial loop: each unique miss computes its own rank.
+#include "kernels.h"
+
+namespace racer {
+namespace {
+
+constexpr uint32_t kEmpty = 0xFFFFFFFFu;
+constexpr int kWave = 64;
+
+__device__ __forceinline__ uint32_t set_of(const EmbView& v, int64_t id) {
+  const unsigned long long h = static_cast<unsigned long long>(id) * 0x9E3779B97F4A7C15ull;
+  return static_cast<uint32_t>(h >> 32) % v.sets;
+}
+
+__device__ __forceinline__ uint32_t ways_of(const EmbView& v, uint32_t set) {
+  return v.full_ways + (set < v.part_sets ? 1u : 0u);
+}
+
+__device__ __forceinline__ int64_t slot_offset(const EmbView& v, uint32_t set, uint32_t way) {
+  const uint32_t logical = way * v.layer_pages + set / v.spp;
+  return static_cast<int64_t>(v.emb_pages[logical]) * static_cast<int64_t>(v.page_size) +
+         static_cast<int64_t>(set % v.spp) * v.row_bytes;
+}
+
+__device__ __forceinline__ int64_t shfl64(int64_t x, int src) {
+  int lo = __shfl(static_cast<int>(x & 0xFFFFFFFFll), src, kWave);
+  int hi = __shfl(static_cast<int>(x >> 32), src, kWave);
+  return (static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo);
+}
+
+__device__ __forceinline__ uint32_t lanes_per_row(uint32_t chunks) {
+  uint32_t l = 1;
+  while (l < 32 && l < chunks) l <<= 1;
+  return l;
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {  // round to nearest even; finite or inf in
+  const uint32_t u = __float_as_uint(f);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// acc (8 fp32 lanes of one 16-byte chunk; fp32 rows use the first 4) <- chunk or acc + chunk
+__device__ __forceinline__ void accumulate_chunk(float acc[8], const uint4& c, bool bf16, bool first) {
+  float v[8];
+  if (bf16) {
+    const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      v[2 * k] = bf16_to_f32(w[k] & 0xFFFFu);
+      v[2 * k + 1] = bf16_to_f32(w[k] >> 16);
+    }
+  } else {
+    v[0] = __uint_as_float(c.x); v[1] = __uint_as_float(c.y);
+    v[2] = __uint_as_float(c.z); v[3] = __uint_as_float(c.w);
+    v[4] = v[5] = v[6] = v[7] = 0.0f;
+  }
+#pragma unroll
+  for (int k = 0; k < 8; ++k) acc[k] = first ? v[k] : acc[k] + v[k];
+}
+
+__device__ __forceinline__ uint4 pack_chunk(const float acc[8], bool bf16) {
+  uint4 r;
+  if (bf16) {
+    r.x = f32_to_bf16(acc[0]) | (f32_to_bf16(acc[1]) << 16);
+    r.y = f32_to_bf16(acc[2]) | (f32_to_bf16(acc[3]) << 16);
+    r.z = f32_to_bf16(acc[4]) | (f32_to_bf16(acc[5]) << 16);
+    r.w = f32_to_bf16(acc[6]) | (f32_to_bf16(acc[7]) << 16);
+  } else {
+    r.x = __float_as_uint(acc[0]); r.y = __float_as_uint(acc[1]);
+    r.z = __float_as_uint(acc[2]); r.w = __float_as_uint(acc[3]);
+  }
+  return r;
+}
+
+// Resolve a `loc` code to a row address (nullptr = all-zero row).
+__device__ __forceinline__ const uint8_t* row_address(const EmbView& v, const MissWs& ws, int64_t loc) {
+  if (loc >= 0) return v.base + loc;
+  if (loc <= -3) return ws.staging + static_cast<uint64_t>(-(loc + 3)) * v.row_bytes;
+  return nullptr;
+}
+
+// One output row handled by `lpr` lanes (`sub` = this lane's number in the group): bag == 1
+// is a raw copy, bag > 1 the fp32 left-to-right sum rounded once.
+template <typename LocFn>
+__device__ __forceinline__ void emit_row(const EmbView& v, const MissWs& ws, uint32_t bag, uint32_t lpr,
+                                         uint32_t sub, uint8_t* dst, LocFn loc_of) {
+  const uint32_t chunks = v.row_bytes / 16;
+  const bool bf16 = v.elem == 1;
+  for (uint32_t c = sub; c < chunks; c += lpr) {
+    uint4 outv;
+    if (bag == 1) {
+      const uint8_t* src = row_address(v, ws, loc_of(0));
+      outv = src ? *reinterpret_cast<const uint4*>(src + 16 * c) : make_uint4(0, 0, 0, 0);
+    } else {
+      float acc[8];
+      for (uint32_t f = 0; f < bag; ++f) {
+        const uint8_t* src = row_address(v, ws, loc_of(f));
+        const uint4 cv = src ? *reinterpret_cast<const uint4*>(src + 16 * c) : make_uint4(0, 0, 0, 0);
+        accumulate_chunk(acc, cv, bf16, f == 0);
+      }
+      outv = pack_chunk(acc, bf16);
+    }
+    *reinterpret_cast<uint4*>(dst + 16 * c) = outv;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Probe + hit gather.  One wavefront takes `lb` consecutive lookups (a whole number of
+// bags, at most 64): lane i owns lookup i, two lookups are probed per step with 32 lanes
+// reading one set's tag line each (128 B, coalesced), then rows are copied with
+// 16-byte lanes.  Misses and the output rows that must wait for them are staged in LDS
+// and appended to the global lists with one atomic per block.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void emb_probe_gather(EmbView v, MissWs ws, const int64_t* __restrict__ ids,
+                                                        uint32_t n, uint32_t bag, uint32_t lb,
+                                                        uint8_t* __restrict__ out,
+                                                        uint8_t* __restrict__ hit_flags, uint32_t batch) {
+  __shared__ uint32_t s_miss[256];
+  __shared__ uint32_t s_def[256];
+  __shared__ uint32_t s_n[2], s_base[2];
+  __shared__ uint32_t s_cnt[3];
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid < 2) s_n[tid] = 0;
+  if (tid < 3) s_cnt[tid] = 0;
+  if (blockIdx.x == 0 && tid < 3) ws.ctr_next[tid] = 0;  // the next call's list counters
+  __syncthreads();
+
+  const uint64_t i0 = (static_cast<uint64_t>(blockIdx.x) * 4 + wave) * lb;
+  const uint64_t i = i0 + lane;
+  const bool active = lane < lb && i < n;
+  const int64_t id = active ? ids[i] : -1;
+  const bool valid = active && id >= 0 && static_cast<uint64_t>(id) < v.rows;
+  const uint32_t id32 = static_cast<uint32_t>(id);
+  const uint32_t set = valid ? set_of(v, id) : 0;
+  const uint32_t nw = valid ? ways_of(v, set) : 0;
+
+  int my_way = -1;
+  if (i0 < n) {
+    const uint32_t l32 = lane & 31, half = lane >> 5;
+#pragma unroll 4
+    for (uint32_t it = 0; it < 32; ++it) {
+      const uint32_t a = 2 * it + half;
+      const uint32_t id_a = __shfl(id32, a, kWave);
+      const uint32_t set_a = __shfl(set, a, kWave);
+      const uint32_t nw_a = __shfl(nw, a, kWave);
+      bool match = false;
+      if (l32 < nw_a) match = v.tags[static_cast<uint64_t>(set_a) * v.w_max + l32] == id_a;
+      const unsigned long long m = __ballot(match);
+      const uint32_t lo = static_cast<uint32_t>(m), hi = static_cast<uint32_t>(m >> 32);
+      if (lane == 2 * it) my_way = lo ? __ffs(lo) - 1 : -1;
+      if (lane == 2 * it + 1) my_way = hi ? __ffs(hi) - 1 : -1;
+    }
+  }
+  const bool hit = valid && my_way >= 0;
+  const bool miss = valid && !hit;
+  int64_t loc = -1;  // zero row (invalid id or padding lane)
+  if (hit) {
+    loc = slot_offset(v, set, static_cast<uint32_t>(my_way));
+    v.stamps[static_cast<uint64_t>(set) * v.w_max + my_way] = batch;
+  } else if (miss) {
+    loc = -2;  // replaced by the staging row once the miss is resolved
+  }
+  if (hit_flags && active) hit_flags[i] = hit ? 1 : 0;
+
+  const unsigned long long hit_m = __ballot(hit), valid_m = __ballot(valid), miss_m = __ballot(miss);
+  const unsigned long long inval_m = __ballot(active && !valid);
+  if (lane == 0) {
+    if (hit_m) atomicAdd(&s_cnt[0], __popcll(hit_m));
+    if (valid_m) atomicAdd(&s_cnt[1], __popcll(valid_m));
+    if (inval_m) atomicAdd(&s_cnt[2], __popcll(inval_m));
+  }
+  const unsigned long long lt_mask = (1ull << lane) - 1ull;
+  if (miss_m) {
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(&s_n[0], __popcll(miss_m));
+    base = __shfl(base, 0, kWave);
+    if (miss) s_miss[base + __popcll(miss_m & lt_mask)] = static_cast<uint32_t>(i);
+  }
+  // an output row waits if any lookup of its bag missed
+  const uint32_t b = lane / bag;  // bag of this lane inside the wave's batch
+  const unsigned long long bag_mask = (bag >= 64 ? ~0ull : ((1ull << bag) - 1ull)) << (b * bag);
+  const bool deferred = active && (miss_m & bag_mask) != 0;
+  const bool def_leader = deferred && (lane % bag) == 0;
+  const unsigned long long def_m = __ballot(def_leader);
+  if (deferred) ws.loc[i] = loc;
+  if (def_m) {
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(&s_n[1], __popcll(def_m));
+    base = __shfl(base, 0, kWave);
+    if (def_leader) s_def[base + __popcll(def_m & lt_mask)] = static_cast<uint32_t>(i / bag);
+  }
+
+  // gather the rows that are complete
+  if (i0 < n) {
+    const uint32_t chunks = v.row_bytes / 16;
+    const uint32_t lpr = lanes_per_row(chunks);
+    const uint32_t rows_per_pass = kWave / lpr;
+    const uint32_t n_out = lb / bag;  // output rows of this wave's batch
+    const uint32_t sub = lane % lpr;
+    for (uint32_t r0 = 0; r0 < n_out; r0 += rows_per_pass) {
+      const uint32_t r = r0 + lane / lpr;                 // output row inside the batch
+      const uint32_t first = (r < n_out ? r : 0) * bag;   // its first lookup lane
+      const bool row_active = r < n_out && (i0 + first) < n;
+      const bool row_deferred = (__shfl(deferred ? 1 : 0, first, kWave) != 0);
+      // all lanes take part in the shuffles; only complete rows are written
+      const uint64_t o = (i0 + first) / bag;
+      if (bag == 1) {
+        const int64_t l0 = shfl64(loc, first);
+        if (row_active && !row_deferred)
+          emit_row(v, ws, 1, lpr, sub, out + o * v.row_bytes, [&](uint32_t) { return l0; });
+      } else {
+        // the shuffles inside the lambda are executed by every lane of the wave
+        const uint32_t chunks_pad = ((chunks + lpr - 1) / lpr) * lpr;
+        for (uint32_t c = sub; c < chunks_pad; c += lpr) {
+          float acc[8];
+          for (uint32_t f = 0; f < bag; ++f) {
+            const int64_t lf = shfl64(loc, first + f);
+            if (row_active && !row_deferred && c < chunks) {
+              const uint8_t* src = row_address(v, ws, lf);
+              const uint4 cv = src ? *reinterpret_cast<const uint4*>(src + 16 * c) : make_uint4(0, 0, 0, 0);
+              accumulate_chunk(acc, cv, v.elem == 1, f == 0);
+            }
+          }
+          if (row_active && !row_deferred && c < chunks)
+            *reinterpret_cast<uint4*>(out + o * v.row_bytes + 16 * c) = pack_chunk(acc, v.elem == 1);
+        }
+      }
+    }
+  }
+
+  __syncthreads();
+  if (tid == 0) {
+    s_base[0] = s_n[0] ? atomicAdd(&ws.ctr[0], s_n[0]) : 0;
+    s_base[1] = s_n[1] ? atomicAdd(&ws.ctr[1], s_n[1]) : 0;
+    if (s_cnt[1]) atomicAdd(&v.counters[kCtrLookups], static_cast<unsigned long long>(s_cnt[1]));
+    if (s_cnt[0]) atomicAdd(&v.counters[kCtrHits], static_cast<unsigned long long>(s_cnt[0]));
+    if (s_cnt[1] - s_cnt[0]) atomicAdd(&v.counters[kCtrMisses], static_cast<unsigned long long>(s_cnt[1] - s_cnt[0]));
+    if (s_cnt[2]) atomicAdd(&v.counters[kCtrInvalid], static_cast<unsigned long long>(s_cnt[2]));
+  }
+  __syncthreads();
+  for (uint32_t k = tid; k < s_n[0]; k += 256) ws.miss_list[s_base[0] + k] = s_miss[k];
+  for (uint32_t k = tid; k < s_n[1]; k += 256) ws.def_list[s_base[1] + k] = s_def[k];
+}
+
+// ---------------------------------------------------------------------------------------
+// Miss path.  All kernels read the list lengths from device memory and return at once
+// when the batch had no miss.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+  x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
+  return x;
+}
+
+// slot of (batch, id) in the dedupe table; inserts when `insert`
+__device__ __forceinline__ uint32_t dedupe_slot(const MissWs& ws, uint32_t batch, uint32_t id32, bool insert) {
+  const unsigned long long key = (static_cast<unsigned long long>(batch) << 32) | id32;
+  uint32_t h = mix32(id32) & ws.hmask;
+  for (;;) {
+    const unsigned long long k = __atomic_load_n(&ws.hkeys[h], __ATOMIC_RELAXED);
+    if (k == key) return h;
+    if ((k >> 32) != batch) {  // older batch or never used: free for this batch
+      if (!insert) return h;   // cannot happen for ids that were inserted
+      const unsigned long long prev = atomicCAS(&ws.hkeys[h], k, key);
+      if (prev == k || prev == key) return h;
+      continue;  // someone else took the slot: look at it again
+    }
+    h = (h + 1) & ws.hmask;
+  }
+}
+
+__global__ __launch_bounds__(256) void miss_dedupe(MissWs ws, const int64_t* __restrict__ ids, uint32_t batch) {
+  const uint32_t n_miss = ws.ctr[0];
+  for (uint32_t m = blockIdx.x * 256 + threadIdx.x; m < n_miss; m += gridDim.x * 256) {
+    const uint32_t i = ws.miss_list[m];
+    const uint32_t id32 = static_cast<uint32_t>(ids[i]);
+    const uint32_t h = dedupe_slot(ws, batch, id32, true);
+    atomicMax(&ws.hvals[h], (static_cast<unsigned long long>(batch) << 32) | (0xFFFFFFFFu - i));
+  }
+}
+
+__global__ __launch_bounds__(256) void miss_link(EmbView v, MissWs ws, const int64_t* __restrict__ ids,
+                                                 uint32_t batch) {
+  const uint32_t n_miss = ws.ctr[0];
+  for (uint32_t m = blockIdx.x * 256 + threadIdx.x; m < n_miss; m += gridDim.x * 256) {
+    const uint32_t i = ws.miss_list[m];
+    const int64_t id = ids[i];
+    const uint32_t id32 = static_cast<uint32_t>(id);
+    const uint32_t h = dedupe_slot(ws, batch, id32, false);
+    const uint32_t first_i = 0xFFFFFFFFu - static_cast<uint32_t>(ws.hvals[h]);
+    if (first_i != i) continue;  // a later duplicate of this id
+    const uint32_t u = atomicAdd(&ws.ctr[2], 1u);
+    const uint32_t set = set_of(v, id);
+    ws.u_i[u] = i;
+    ws.u_id[u] = id32;
+    ws.u_set[u] = set;
+    ws.hslot_u[h] = u;
+    const unsigned long long prev =
+        atomicExch(&ws.heads[mix32(set) & ws.headmask], (static_cast<unsigned long long>(batch) << 32) | u);
+    ws.u_next[u] = (prev >> 32) == batch ? static_cast<int32_t>(static_cast<uint32_t>(prev)) : -1;
+  }
+}
+
+// Half a wavefront per unique miss: lane = way.  rank = number of unique misses of the same
+// set that occur earlier in the batch; the miss takes the rank-th victim candidate of the
+// set in (empty ways by index, then (stamp, way) ascending among stamps older than the batch).
+__global__ __launch_bounds__(256) void miss_decide(EmbView v, MissWs ws, uint32_t batch) {
+  const uint32_t n_unique = ws.ctr[2];
+  const uint32_t lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
+  const uint32_t wave = (blockIdx.x * 256 + threadIdx.x) >> 6, n_waves = (gridDim.x * 256) >> 6;
+  for (uint32_t u0 = wave * 2; u0 < n_unique; u0 += n_waves * 2) {
+    const uint32_t u = u0 + half;
+    const bool act = u < n_unique;
+    uint32_t set = 0, my_i = 0, rank = 0, nw = 0;
+    if (act) {
+      set = ws.u_set[u];
+      my_i = ws.u_i[u];
+      nw = ways_of(v, set);
+      const unsigned long long hv = ws.heads[mix32(set) & ws.headmask];
+      int32_t cur = (hv >> 32) == batch ? static_cast<int32_t>(static_cast<uint32_t>(hv)) : -1;
+      while (cur >= 0) {
+        if (ws.u_set[cur] == set && ws.u_i[cur] < my_i) ++rank;
+        cur = ws.u_next[cur];
+      }
+    }
+    uint32_t tg = kEmpty, sp = 0;
+    const bool way_ok = act && l32 < nw;
+    if (way_ok) {
+      tg = v.tags[static_cast<uint64_t>(set) * v.w_max + l32];
+      sp = v.stamps[static_cast<uint64_t>(set) * v.w_max + l32];
+    }
+    const bool cand = way_ok && (tg == kEmpty || sp < batch);
+    const unsigned long long key =
+        !cand ? ~0ull : (tg == kEmpty ? l32 : ((1ull << 40) | (static_cast<unsigned long long>(sp) << 5) | l32));
+    uint32_t pos = 0;
+    for (uint32_t j = 0; j < 32; ++j) {
+      const unsigned long long kj = static_cast<unsigned long long>(shfl64(static_cast<int64_t>(key), half * 32 + j));
+      pos += (kj < key) ? 1u : 0u;
+    }
+    const unsigned long long vm = __ballot(cand && pos == rank);
+    const uint32_t mine = half ? static_cast<uint32_t>(vm >> 32) : static_cast<uint32_t>(vm);
+    const int32_t way = mine ? __ffs(mine) - 1 : -1;
+    const uint32_t victim_tag = __shfl(tg, half * 32 + (way >= 0 ? way : 0), kWave);
+    if (act && l32 == 0) {
+      ws.u_way[u] = way;
+      atomicAdd(&v.counters[kCtrUnique], 1ull);
+      if (way >= 0) {
+        atomicAdd(&v.counters[kCtrInserted], 1ull);
+        if (victim_tag != kEmpty) atomicAdd(&v.counters[kCtrEvicted], 1ull);
+      } else {
+        atomicAdd(&v.counters[kCtrBypassed], 1ull);
+      }
+    }
+  }
+}
+
+// every missing lookup, duplicates included, learns the staging row of its id
+__global__ __launch_bounds__(256) void miss_resolve(MissWs ws, const int64_t* __restrict__ ids, uint32_t batch) {
+  const uint32_t n_miss = ws.ctr[0];
+  for (uint32_t m = blockIdx.x * 256 + threadIdx.x; m < n_miss; m += gridDim.x * 256) {
+    const uint32_t i = ws.miss_list[m];
+    const uint32_t h = dedupe_slot(ws, batch, static_cast<uint32_t>(ids[i]), false);
+    ws.loc[i] = -(static_cast<int64_t>(ws.hslot_u[h]) + 3);
+  }
+}
+
+// Apply the decisions: new tag and stamp, then one read of the row from the pinned host
+// table (zero-copy over PCIe) into the staging row and, if inserted, into the pool slot.
+__global__ __launch_bounds__(256) void miss_apply_fetch(EmbView v, MissWs ws, uint32_t batch) {
+  const uint32_t n_unique = ws.ctr[2];
+  const uint32_t lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
+  const uint32_t wave = (blockIdx.x * 256 + threadIdx.x) >> 6, n_waves = (gridDim.x * 256) >> 6;
+  const uint32_t chunks = v.row_bytes / 16;
+  for (uint32_t u0 = wave * 2; u0 < n_unique; u0 += n_waves * 2) {
+    const uint32_t u = u0 + half;
+    if (u >= n_unique) continue;
+    const uint32_t id32 = ws.u_id[u], set = ws.u_set[u];
+    const int32_t way = ws.u_way[u];
+    uint8_t* dst = nullptr;
+    if (way >= 0) {
+      dst = v.base + slot_offset(v, set, static_cast<uint32_t>(way));
+      if (l32 == 0) {
+        v.tags[static_cast<uint64_t>(set) * v.w_max + way] = id32;
+        v.stamps[static_cast<uint64_t>(set) * v.w_max + way] = batch;
+      }
+    }
+    const uint8_t* src = v.table + static_cast<uint64_t>(id32) * v.row_bytes;
+    uint8_t* stg = ws.staging + static_cast<uint64_t>(u) * v.row_bytes;
+    for (uint32_t c = l32; c < chunks; c += 32) {
+      const uint4 val = *reinterpret_cast<const uint4*>(src + 16 * c);
+      *reinterpret_cast<uint4*>(stg + 16 * c) = val;
+      if (dst) *reinterpret_cast<uint4*>(dst + 16 * c) = val;
+    }
+  }
+}
+
+// Output rows that waited for a miss.
+__global__ __launch_bounds__(256) void emb_deferred_gather(EmbView v, MissWs ws, uint32_t bag,
+                                                           uint8_t* __restrict__ out) {
+  const uint32_t n_def = ws.ctr[1];
+  const uint32_t chunks = v.row_bytes / 16;
+  const uint32_t lpr = lanes_per_row(chunks);
+  const uint32_t gid = blockIdx.x * 256 + threadIdx.x;
+  const uint32_t sub = gid % lpr;
+  const uint32_t groups = gridDim.x * 256 / lpr;
+  for (uint32_t k = gid / lpr; k < n_def; k += groups) {
+    const uint64_t o = ws.def_list[k];
+    emit_row(v, ws, bag, lpr, sub, out + o * v.row_bytes,
+             [&](uint32_t f) { return ws.loc[o * bag + f]; });
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Split shrink: per set, evict down to the new way count (empties first, then least
+// (stamp, way)), move survivors of the removed ways into the vacated lower ways.
+// Half a wavefront per set, lane = way.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void emb_shrink_sets(EmbView v, uint32_t old_full, uint32_t old_part_sets) {
+  const uint32_t lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
+  const uint32_t wave = (blockIdx.x * 256 + threadIdx.x) >> 6, n_waves = (gridDim.x * 256) >> 6;
+  const uint32_t chunks = v.row_bytes / 16;
+  for (uint32_t s0 = wave * 2; s0 < v.sets; s0 += n_waves * 2) {
+    const uint32_t s = s0 + half;
+    const bool act = s < v.sets;
+    const uint32_t a = act ? old_full + (s < old_part_sets ? 1u : 0u) : 0;
+    const uint32_t b = act ? ways_of(v, s) : 0;
+    const bool shrinks = b < a;
+    uint32_t tg = kEmpty, sp = 0;
+    if (shrinks && l32 < a) {
+      tg = v.tags[static_cast<uint64_t>(s) * v.w_max + l32];
+      sp = v.stamps[static_cast<uint64_t>(s) * v.w_max + l32];
+    }
+    const bool live = tg != kEmpty;
+    const unsigned long long live_all = __ballot(live);
+    const uint32_t live_m = half ? static_cast<uint32_t>(live_all >> 32) : static_cast<uint32_t>(live_all);
+    const uint32_t n_live = __popc(live_m);
+    const uint32_t n_evict = n_live > b ? n_live - b : 0;
+    // rank among live entries by (stamp, way) ascending
+    const unsigned long long key = live ? ((static_cast<unsigned long long>(sp) << 5) | l32) : ~0ull;
+    uint32_t rank = 0;
+    for (uint32_t j = 0; j < 32; ++j) {
+      const unsigned long long kj = static_cast<unsigned long long>(shfl64(static_cast<int64_t>(key), half * 32 + j));
+      rank += (kj < key) ? 1u : 0u;
+    }
+    const bool evicted = live && rank < n_evict;
+    const bool survivor = live && !evicted;
+    const bool mover = survivor && l32 >= b;
+    const bool hole = shrinks && l32 < b && !survivor;
+    const unsigned long long mover_all = __ballot(mover), hole_all = __ballot(hole);
+    const uint32_t mover_m = half ? static_cast<uint32_t>(mover_all >> 32) : static_cast<uint32_t>(mover_all);
+    const uint32_t hole_m = half ? static_cast<uint32_t>(hole_all >> 32) : static_cast<uint32_t>(hole_all);
+    const uint32_t lt = (1u << l32) - 1u;
+    // the k-th hole receives the k-th mover
+    int src_way = -1;
+    if (hole) {
+      const uint32_t k = __popc(hole_m & lt);
+      uint32_t mm = mover_m;
+      for (uint32_t q = 0; q < k && mm; ++q) mm &= mm - 1;
+      if (mm) src_way = __ffs(mm) - 1;
+    }
+    const uint32_t in_tag = __shfl(tg, half * 32 + (src_way >= 0 ? src_way : 0), kWave);
+    const uint32_t in_stamp = __shfl(sp, half * 32 + (src_way >= 0 ? src_way : 0), kWave);
+    if (shrinks && l32 < a) {
+      uint32_t new_tag = kEmpty, new_stamp = 0;
+      if (l32 < b) {
+        if (survivor) { new_tag = tg; new_stamp = sp; }
+        else if (src_way >= 0) { new_tag = in_tag; new_stamp = in_stamp; }
+      }
+      if (new_tag != tg || new_stamp != sp) {
+        v.tags[static_cast<uint64_t>(s) * v.w_max + l32] = new_tag;
+        v.stamps[static_cast<uint64_t>(s) * v.w_max + l32] = new_stamp;
+      }
+    }
+    const unsigned long long ev_all = __ballot(evicted);
+    const uint32_t ev_m = half ? static_cast<uint32_t>(ev_all >> 32) : static_cast<uint32_t>(ev_all);
+    if (act && l32 == 0) {
+      if (ev_m) atomicAdd(&v.counters[kCtrShrinkEvicted], static_cast<unsigned long long>(__popc(ev_m)));
+      if (mover_m) atomicAdd(&v.counters[kCtrShrinkMoved], static_cast<unsigned long long>(__popc(mover_m)));
+    }
+    // row moves: destination ways are below every source way, and a destination is never
+    // a later mover's source, so moving in ascending order is safe
+    uint32_t mm = mover_m, hm = hole_m;
+    while (mm) {
+      const uint32_t from = __ffs(mm) - 1, to = __ffs(hm) - 1;
+      mm &= mm - 1;
+      hm &= hm - 1;
+      // old geometry for the source: the page of a removed way is still mapped in emb_pages
+      const uint8_t* src = v.base + slot_offset(v, s, from);
+      uint8_t* dst = v.base + slot_offset(v, s, to);
+      for (uint32_t c = l32; c < chunks; c += 32)
+        *reinterpret_cast<uint4*>(dst + 16 * c) = *reinterpret_cast<const uint4*>(src + 16 * c);
+    }
+  }
+}
+
+__global__ void fill_u32_kernel(uint32_t* p, uint64_t n, uint32_t value) {
+  for (uint64_t k = blockIdx.x * static_cast<uint64_t>(blockDim.x) + threadIdx.x; k < n;
+       k += static_cast<uint64_t>(gridDim.x) * blockDim.x)
+    p[k] = value;
+}
+
+}  // namespace
+
+hipError_t launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  const uint32_t blocks = static_cast<uint32_t>(n / 256 + 1 < 4096 ? n / 256 + 1 : 4096);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks), dim3(256), 0, stream, p, n, value);
+  return hipGetLastError();
+}
+
+hipError_t launch_emb_lookup(const EmbView& v, const MissWs& ws, const int64_t* ids, uint32_t n,
+                             uint32_t bag, uint8_t* out, uint8_t* hit_flags, uint32_t batch,
+                             hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  const uint32_t lb = (64 / bag) * bag;
+  const uint32_t per_block = 4 * lb;
+  const uint32_t blocks = (n + per_block - 1) / per_block;
+  hipLaunchKernelGGL(emb_probe_gather, dim3(blocks), dim3(256), 0, stream, v, ws, ids, n, bag, lb, out, hit_flags, batch);
+  // the miss kernels size themselves from device counters; a modest grid keeps the
+  // no-miss case cheap and still saturates PCIe when a cold batch arrives
+  const uint32_t mblocks = n / 256 + 1 < 1024 ? n / 256 + 1 : 1024;
+  hipLaunchKernelGGL(miss_dedupe, dim3(mblocks), dim3(256), 0, stream, ws, ids, batch);
+  hipLaunchKernelGGL(miss_link, dim3(mblocks), dim3(256), 0, stream, v, ws, ids, batch);
+  hipLaunchKernelGGL(miss_decide, dim3(mblocks), dim3(256), 0, stream, v, ws, batch);
+  hipLaunchKernelGGL(miss_resolve, dim3(mblocks), dim3(256), 0, stream, ws, ids, batch);
+  hipLaunchKernelGGL(miss_apply_fetch, dim3(mblocks), dim3(256), 0, stream, v, ws, batch);
+  hipLaunchKernelGGL(emb_deferred_gather, dim3(mblocks), dim3(256), 0, stream, v, ws, bag, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_emb_shrink(const EmbView& v, uint32_t old_full, uint32_t old_part_sets, hipStream_t stream) {
+  const uint32_t waves_needed = (v.sets + 1) / 2;
+  uint32_t blocks = (waves_needed + 3) / 4;
+  if (blocks > 8192) blocks = 8192;
+  if (blocks == 0) blocks = 1;
+  hipLaunchKernelGGL(emb_shrink_sets, dim3(blocks), dim3(256), 0, stream, v, old_full, old_part_sets);
+  return hipGetLastError();
+}
+
+}  // namespace racer

@@ -1,0 +1,500 @@
+// HSTU layer kernels for gfx950 (paper Sec. II-A/II-B "Compute" stage; the layer equations
+// are the published HSTU form):
+//   Xn = LayerNorm(X);  [U|V|Q|K] = SiLU(Xn W1 + b1);  K,V of the new tokens -> KV pages
+//   O_i = (1/n) sum_{j<=p_i} SiLU(q_i.k_j + pos[min(p_i-j, n_pos-1)] + time[bucket(ts_p-ts_j)]) v_j
+//   Y = X + (LayerNorm(O) * U) W2 + b2
+// bf16 models run on MFMA (v_mfma_f32_32x32x16_bf16) with fp32 accumulation; the small
+// fp32 configuration uses plain FMA kernels.
+//
+// KV page layout (one page = page_tokens tokens of every layer):
+//   [layer][K|V][head] blocks of page_tokens*d_h elements;
+//   a K block is [token][d_h]; a V block is stored transposed, [d_h][token], so that the
+//   second product's matrix operand (contraction over keys) is read key-contiguous.
+#include "kernels.h"
+
+namespace racer {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+__device__ __forceinline__ uint16_t f2bf(float f) {
+  const uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return static_cast<uint16_t>((u >> 16) | 0x40);
+  return static_cast<uint16_t>((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+__device__ __forceinline__ float load_elem(const float* p, uint64_t i) { return p[i]; }
+__device__ __forceinline__ float load_elem(const bf16_t* p, uint64_t i) { return bf2f(p[i].bits); }
+__device__ __forceinline__ void store_elem(float* p, uint64_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void store_elem(bf16_t* p, uint64_t i, float v) { p[i].bits = f2bf(v); }
+
+__device__ __forceinline__ float silu(float x) { return x / (1.0f + __expf(-x)); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+__device__ __forceinline__ uint32_t time_bucket(long long dt, uint32_t n_time) {
+  const unsigned long long v = dt > 1 ? static_cast<unsigned long long>(dt) : 1ull;
+  const uint32_t b = 63u - static_cast<uint32_t>(__clzll(static_cast<long long>(v)));
+  return b < n_time - 1 ? b : n_time - 1;
+}
+
+// byte offset of the K (kv = 0) or V (kv = 1) block of (layer, head) inside a page
+__device__ __forceinline__ uint64_t kv_block_offset(const HstuDims& hd, uint32_t layer, uint32_t kv, uint32_t head,
+                                                    uint32_t esize) {
+  return ((static_cast<uint64_t>(layer) * 2 + kv) * hd.H + head) * hd.pt * hd.dh * esize;
+}
+
+// ---------------------------------------------------------------------------------------
+// LayerNorm over d (optionally times a gate row), one wavefront per row, two-pass in fp32
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_rows(const T* __restrict__ x, const float* __restrict__ g,
+                                                      const float* __restrict__ b, const T* __restrict__ gate,
+                                                      T* __restrict__ y, uint32_t N, uint32_t d, float eps) {
+  const uint32_t lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= N) return;
+  float v[16];
+  float s = 0.0f;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const uint32_t c = lane + 64 * k;
+    v[k] = c < d ? load_elem(x, static_cast<uint64_t>(row) * d + c) : 0.0f;
+    s += v[k];
+  }
+  const float mean = wave_sum(s) / d;
+  float q = 0.0f;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const uint32_t c = lane + 64 * k;
+    const float dv = c < d ? v[k] - mean : 0.0f;
+    q += dv * dv;
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / d + eps);
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const uint32_t c = lane + 64 * k;
+    if (c < d) {
+      float o = (v[k] - mean) * rstd * g[c] + b[c];
+      if (gate) o *= load_elem(gate, static_cast<uint64_t>(row) * d + c);
+      store_elem(y, static_cast<uint64_t>(row) * d + c, o);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Epilogues
+// ---------------------------------------------------------------------------------------
+template <typename T>
+struct FrontEpilogue {  // SiLU(acc + b1), split U | V | Q | K, K and V into the pages
+  HstuDims hd;
+  uint32_t layer;
+  const float* b1;
+  T* u;
+  T* q;
+  KvView kv;
+  const ReqDev* reqs;
+  const uint32_t* row_req;
+  const int32_t* page_tables;
+
+  __device__ __forceinline__ void operator()(uint32_t row, uint32_t col, float acc) const {
+    const float z = silu(acc + b1[col]);
+    const uint32_t which = col / hd.d, c = col % hd.d;
+    if (which == 0) { store_elem(u, static_cast<uint64_t>(row) * hd.d + c, z); return; }
+    if (which == 2) { store_elem(q, static_cast<uint64_t>(row) * hd.d + c, z); return; }
+    const ReqDev rq = reqs[row_req[row]];
+    const uint32_t pos = rq.prefix_len + (row - rq.x_off);
+    const int32_t page = page_tables[rq.page_table_off + pos / hd.pt];
+    if (page < 0 || static_cast<uint32_t>(page) >= kv.n_pages) {
+      atomicAdd(&kv.counters[kCtrBadPages], 1ull);
+      return;
+    }
+    const uint32_t head = c / hd.dh, cc = c % hd.dh, tok = pos % hd.pt;
+    T* blk = reinterpret_cast<T*>(kv.base + static_cast<uint64_t>(page) * kv.page_size +
+                                  kv_block_offset(hd, layer, which == 1 ? 1 : 0, head, sizeof(T)));
+    if (which == 3) store_elem(blk, static_cast<uint64_t>(tok) * hd.dh + cc, z);   // K: [token][d_h]
+    else store_elem(blk, static_cast<uint64_t>(cc) * hd.pt + tok, z);              // V: [d_h][token]
+  }
+};
+
+template <typename T>
+struct BackEpilogue {  // y = x + acc + b2
+  uint32_t d;
+  const float* b2;
+  const T* x;
+  T* y;
+  __device__ __forceinline__ void operator()(uint32_t row, uint32_t col, float acc) const {
+    const uint64_t i = static_cast<uint64_t>(row) * d + col;
+    store_elem(y, i, load_elem(x, i) + acc + b2[col]);
+  }
+};
+
+// ---------------------------------------------------------------------------------------
+// bf16 GEMM on MFMA: C[M][Nout] = A[M][K] * Bt[Nout][K]^T, block tile 128 x 64, four
+// wavefronts of 32 rows x 64 columns each, K staged through LDS 64 at a time.
+// Operand layout of v_mfma_f32_32x32x16_bf16: lane (g = lane/32, i = lane%32) supplies row
+// (A) or column (B) i with eight consecutive k of its half g; the result lane holds column
+// i and rows 8*(r/4) + 4*g + r%4 for r = 0..15.
+// ---------------------------------------------------------------------------------------
+constexpr int kLdsPad = 8;
+
+template <typename Epi>
+__global__ __launch_bounds__(256) void gemm_bf16_mfma(const uint16_t* __restrict__ A, const uint16_t* __restrict__ Bt,
+                                                      uint32_t M, uint32_t K, Epi epi) {
+  __shared__ __attribute__((aligned(16))) uint16_t As[128][64 + kLdsPad];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[64][64 + kLdsPad];
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, li = lane & 31;
+  const uint32_t m0 = blockIdx.x * 128, n0 = blockIdx.y * 64;
+  f32x16 acc[2];
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[cb][r] = 0.0f;
+
+  for (uint32_t k0 = 0; k0 < K; k0 += 64) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const uint32_t c = tid + 256 * it, row = c >> 3, part = c & 7;
+      uint4 val = make_uint4(0, 0, 0, 0);
+      if (m0 + row < M) val = *reinterpret_cast<const uint4*>(A + static_cast<uint64_t>(m0 + row) * K + k0 + part * 8);
+      *reinterpret_cast<uint4*>(&As[row][part * 8]) = val;
+    }
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const uint32_t c = tid + 256 * it, row = c >> 3, part = c & 7;
+      *reinterpret_cast<uint4*>(&Bs[row][part * 8]) =
+          *reinterpret_cast<const uint4*>(Bt + static_cast<uint64_t>(n0 + row) * K + k0 + part * 8);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&As[32 * wave + li][16 * st + 8 * g]));
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) {
+        const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Bs[32 * cb + li][16 * st + 8 * g]));
+        acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[cb], 0, 0, 0);
+      }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const uint32_t row = m0 + 32 * wave + 8 * (r / 4) + 4 * g + (r % 4);
+      if (row < M) epi(row, n0 + 32 * cb + li, acc[cb][r]);
+    }
+}
+
+// fp32 GEMM for the small configuration: one thread per output, W is [K][Nout]
+template <typename Epi>
+__global__ __launch_bounds__(256) void gemm_f32_simple(const float* __restrict__ A, const float* __restrict__ W,
+                                                       uint32_t M, uint32_t K, uint32_t Nout, Epi epi) {
+  const uint64_t idx = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (idx >= static_cast<uint64_t>(M) * Nout) return;
+  const uint32_t row = static_cast<uint32_t>(idx / Nout), col = static_cast<uint32_t>(idx % Nout);
+  float acc = 0.0f;
+  for (uint32_t k = 0; k < K; ++k) acc = fmaf(A[static_cast<uint64_t>(row) * K + k], W[static_cast<uint64_t>(k) * Nout + col], acc);
+  epi(row, col, acc);
+}
+
+// ---------------------------------------------------------------------------------------
+// fp32 attention: one wavefront per (query row, head); lanes stride over the keys
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attention_f32(HstuDims hd, uint32_t layer, const float* __restrict__ q,
+                                                     const float* __restrict__ pos, const float* __restrict__ time,
+                                                     KvView kv, const ReqDev* __restrict__ reqs,
+                                                     const uint32_t* __restrict__ row_req, uint32_t N,
+                                                     const int32_t* __restrict__ page_tables,
+                                                     const long long* __restrict__ ts, float* __restrict__ o) {
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t item = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= N * hd.H) return;
+  const uint32_t row = item / hd.H, h = item % hd.H;
+  const ReqDev rq = reqs[row_req[row]];
+  const uint32_t p = rq.prefix_len + (row - rq.x_off);
+  const long long ts_p = ts[rq.ts_off + p];
+  float qv[64], acc[64];
+#pragma unroll
+  for (int c = 0; c < 64; ++c) {
+    qv[c] = c < static_cast<int>(hd.dh) ? q[static_cast<uint64_t>(row) * hd.d + h * hd.dh + c] : 0.0f;
+    acc[c] = 0.0f;
+  }
+  const float* pos_h = pos + (static_cast<uint64_t>(layer) * hd.H + h) * hd.n_pos;
+  const float* time_h = time + (static_cast<uint64_t>(layer) * hd.H + h) * hd.n_time;
+  const uint64_t koff = kv_block_offset(hd, layer, 0, h, 4), voff = kv_block_offset(hd, layer, 1, h, 4);
+  for (uint32_t j = lane; j <= p; j += 64) {
+    const int32_t page = page_tables[rq.page_table_off + j / hd.pt];
+    if (page < 0 || static_cast<uint32_t>(page) >= kv.n_pages) {
+      atomicAdd(&kv.counters[kCtrBadPages], 1ull);
+      continue;
+    }
+    const uint8_t* pb = kv.base + static_cast<uint64_t>(page) * kv.page_size;
+    const float* kr = reinterpret_cast<const float*>(pb + koff) + static_cast<uint64_t>(j % hd.pt) * hd.dh;
+    const float* vt = reinterpret_cast<const float*>(pb + voff) + (j % hd.pt);
+    float s = 0.0f;
+#pragma unroll
+    for (int c = 0; c < 64; ++c)
+      if (c < static_cast<int>(hd.dh)) s = fmaf(qv[c], kr[c], s);
+    const uint32_t rel = p - j < hd.n_pos - 1 ? p - j : hd.n_pos - 1;
+    s += pos_h[rel] + time_h[time_bucket(ts_p - ts[rq.ts_off + j], hd.n_time)];
+    const float a = s / (1.0f + expf(-s));
+#pragma unroll
+    for (int c = 0; c < 64; ++c)
+      if (c < static_cast<int>(hd.dh)) acc[c] = fmaf(a, vt[static_cast<uint64_t>(c) * hd.pt], acc[c]);
+  }
+#pragma unroll
+  for (int c = 0; c < 64; ++c) {
+    if (c < static_cast<int>(hd.dh)) {
+      const float t = wave_sum(acc[c]);
+      if (lane == 0) o[static_cast<uint64_t>(row) * hd.d + h * hd.dh + c] = t * hd.inv_n;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// bf16 paged attention on MFMA, d_h = 64.  A block of four wavefronts owns 128 consecutive
+// queries of one request and one head; it walks the key tiles (64 keys) from position 0 to
+// its last query, staging K [key][d_h] and V^T [d_h][key] of the tile in LDS through the
+// page table.  Each wavefront computes S^T = K Q^T for its 32 queries (keys x queries, so
+// a lane ends up holding one query and 16 keys), applies bias, SiLU and the causal mask in
+// registers, and feeds the bf16 result straight back as the second operand of
+// O^T += V^T P^T: the accumulator layout of the first product is exactly the operand layout
+// of the second, so the scores never leave registers.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attention_bf16_mfma(HstuDims hd, uint32_t layer, const uint16_t* __restrict__ q,
+                                                           const float* __restrict__ pos,
+                                                           const float* __restrict__ time, KvView kv,
+                                                           const ReqDev* __restrict__ reqs,
+                                                           const uint32_t* __restrict__ tiles,
+                                                           const int32_t* __restrict__ page_tables,
+                                                           const long long* __restrict__ ts,
+                                                           uint16_t* __restrict__ o) {
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[64][64 + kLdsPad];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[64][64 + kLdsPad];
+  __shared__ long long s_ts[64];
+  __shared__ float s_time[64];
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, li = lane & 31;
+  const uint32_t r = tiles[2 * blockIdx.x], qt = tiles[2 * blockIdx.x + 1], h = blockIdx.y;
+  const ReqDev rq = reqs[r];
+  const uint32_t P = rq.prefix_len, T = rq.new_len, S = P + T;
+  const uint32_t q0 = qt * 128;                 // first query (index among the new tokens) of the block
+  const uint32_t qi = q0 + 32 * wave + li;      // this lane's query
+  const bool q_ok = qi < T;
+  const uint32_t p = P + qi;                    // its absolute position
+  const uint32_t wave_last = P + (q0 + 32 * wave + 31 < T - 1 ? q0 + 32 * wave + 31 : T - 1);
+  const uint32_t block_last = P + (q0 + 127 < T - 1 ? q0 + 127 : T - 1);
+  if (tid < 64) s_time[tid] = tid < hd.n_time ? time[(static_cast<uint64_t>(layer) * hd.H + h) * hd.n_time + tid] : 0.0f;
+  const float* pos_h = pos + (static_cast<uint64_t>(layer) * hd.H + h) * hd.n_pos;
+  const long long ts_q = q_ok ? ts[rq.ts_off + p] : 0;
+
+  // Q^T operand: lane (g, li) holds query li, d_h elements 16*st + 8*g .. +8
+  bf16x8 qf[4];
+#pragma unroll
+  for (int st = 0; st < 4; ++st) {
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (q_ok) val = *reinterpret_cast<const uint4*>(q + static_cast<uint64_t>(rq.x_off + qi) * hd.d + h * 64 + 16 * st + 8 * g);
+    qf[st] = __builtin_bit_cast(bf16x8, val);
+  }
+  f32x16 oacc[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) oacc[b][e] = 0.0f;
+
+  const uint64_t koff = kv_block_offset(hd, layer, 0, h, 2), voff = kv_block_offset(hd, layer, 1, h, 2);
+  const uint32_t n_tiles = block_last / 64 + 1;
+  for (uint32_t kt = 0; kt < n_tiles; ++kt) {
+    const uint32_t j0 = kt * 64;
+    // ---- stage the tile ----
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const uint32_t c = tid + 256 * it, row = c >> 3, part = c & 7;
+      // K: row = key, part = 8 d_h elements
+      uint4 kval = make_uint4(0, 0, 0, 0);
+      const uint32_t j = j0 + row;
+      if (j < S) {
+        const int32_t page = page_tables[rq.page_table_off + j / hd.pt];
+        if (page >= 0 && static_cast<uint32_t>(page) < kv.n_pages)
+          kval = *reinterpret_cast<const uint4*>(kv.base + static_cast<uint64_t>(page) * kv.page_size + koff +
+                                                 (static_cast<uint64_t>(j % hd.pt) * 64 + part * 8) * 2);
+        else if (part == 0) atomicAdd(&kv.counters[kCtrBadPages], 1ull);
+      }
+      *reinterpret_cast<uint4*>(&Ks[row][part * 8]) = kval;
+      // V^T: row = d_h element, part = 8 consecutive keys (inside one page: page_tokens % 8 == 0)
+      uint4 vval = make_uint4(0, 0, 0, 0);
+      const uint32_t jv = j0 + part * 8;
+      if (jv < S) {
+        const int32_t page = page_tables[rq.page_table_off + jv / hd.pt];
+        if (page >= 0 && static_cast<uint32_t>(page) < kv.n_pages) {
+          vval = *reinterpret_cast<const uint4*>(kv.base + static_cast<uint64_t>(page) * kv.page_size + voff +
+                                                 (static_cast<uint64_t>(row) * hd.pt + jv % hd.pt) * 2);
+          if (jv + 8 > S) {  // keys past the end of the sequence hold whatever the page held before
+            uint32_t w[4] = {vval.x, vval.y, vval.z, vval.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (jv + e >= S) w[e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+            vval = make_uint4(w[0], w[1], w[2], w[3]);
+          }
+        }
+      }
+      *reinterpret_cast<uint4*>(&Vs[row][part * 8]) = vval;
+    }
+    if (tid < 64) s_ts[tid] = (j0 + tid < S) ? ts[rq.ts_off + j0 + tid] : 0;
+    __syncthreads();
+
+    // ---- two 32-key sub-blocks ----
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb) {
+      const uint32_t kb = j0 + 32 * sb;
+      if (kb > wave_last) continue;  // every key of the sub-block lies after every query of this wave
+      f32x16 sacc;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sacc[e] = 0.0f;
+#pragma unroll
+      for (int st = 0; st < 4; ++st) {
+        const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Ks[32 * sb + li][16 * st + 8 * g]));
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], sacc, 0, 0, 0);
+      }
+      // sacc[e]: key kb + 8*(e/4) + 4*g + e%4, query li
+      uint32_t pk[8];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const uint32_t jl = 32 * sb + 8 * (e / 4) + 4 * g + (e % 4);
+        const uint32_t j = j0 + jl;
+        float a = 0.0f;
+        if (q_ok && j <= p) {
+          const uint32_t rel = p - j < hd.n_pos - 1 ? p - j : hd.n_pos - 1;
+          const float s = sacc[e] + pos_h[rel] + s_time[time_bucket(ts_q - s_ts[jl], hd.n_time)];
+          a = silu(s);
+        }
+        const uint32_t bits = f2bf(a);
+        if (e & 1) pk[e >> 1] |= bits << 16;
+        else pk[e >> 1] = bits;
+      }
+      // P^T operand of step s2 = elements 8*s2 .. 8*s2+7: keys kb + 16*s2 + {4g..4g+3, 8+4g..8+4g+3}
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const bf16x8 pf = __builtin_bit_cast(bf16x8, make_uint4(pk[4 * s2], pk[4 * s2 + 1], pk[4 * s2 + 2], pk[4 * s2 + 3]));
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          const uint16_t* vrow = &Vs[32 * db + li][32 * sb + 16 * s2 + 4 * g];
+          const uint2 lo = *reinterpret_cast<const uint2*>(vrow);
+          const uint2 hi = *reinterpret_cast<const uint2*>(vrow + 8);
+          const bf16x8 vf = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[db], 0, 0, 0);
+        }
+      }
+    }
+    __syncthreads();
+  }
+  // oacc[db][e]: d_h element 32*db + 8*(e/4) + 4*g + e%4 of query li
+  if (q_ok) {
+    uint16_t* orow = o + static_cast<uint64_t>(rq.x_off + qi) * hd.d + h * 64;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        uint2 w;
+        w.x = f2bf(oacc[db][4 * e4] * hd.inv_n) | (static_cast<uint32_t>(f2bf(oacc[db][4 * e4 + 1] * hd.inv_n)) << 16);
+        w.y = f2bf(oacc[db][4 * e4 + 2] * hd.inv_n) | (static_cast<uint32_t>(f2bf(oacc[db][4 * e4 + 3] * hd.inv_n)) << 16);
+        *reinterpret_cast<uint2*>(orow + 32 * db + 8 * e4 + 4 * g) = w;
+      }
+  }
+}
+
+template <typename T>
+__global__ void transpose_kernel(const T* __restrict__ w, T* __restrict__ wt, uint32_t rows, uint32_t cols) {
+  __shared__ T tile[32][33];
+  const uint32_t bx = blockIdx.x * 32, by = blockIdx.y * 32;
+  for (uint32_t yy = threadIdx.y; yy < 32; yy += 8)
+    if (by + yy < rows && bx + threadIdx.x < cols) tile[yy][threadIdx.x] = w[static_cast<uint64_t>(by + yy) * cols + bx + threadIdx.x];
+  __syncthreads();
+  for (uint32_t yy = threadIdx.y; yy < 32; yy += 8)
+    if (bx + yy < cols && by + threadIdx.x < rows) wt[static_cast<uint64_t>(bx + yy) * rows + by + threadIdx.x] = tile[threadIdx.x][yy];
+}
+
+}  // namespace
+
+hipError_t launch_layernorm(const HstuDims& hd, const void* x, const float* g, const float* b, const void* gate,
+                            void* y, uint32_t N, hipStream_t stream) {
+  if (N == 0) return hipSuccess;
+  const dim3 grid((N + 3) / 4), block(256);
+  if (hd.elem == 1)
+    hipLaunchKernelGGL(layernorm_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t*>(x), g, b,
+                       static_cast<const bf16_t*>(gate), static_cast<bf16_t*>(y), N, hd.d, hd.eps);
+  else
+    hipLaunchKernelGGL(layernorm_rows<float>, grid, block, 0, stream, static_cast<const float*>(x), g, b,
+                       static_cast<const float*>(gate), static_cast<float*>(y), N, hd.d, hd.eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_front(const HstuDims& hd, uint32_t layer, const void* xn, const void* w1, const float* b1,
+                             void* u, void* q, const KvView& kv, const StepLists& sl, const int32_t* page_tables,
+                             hipStream_t stream) {
+  if (sl.N == 0) return hipSuccess;
+  if (hd.elem == 1) {
+    FrontEpilogue<bf16_t> epi{hd, layer, b1, static_cast<bf16_t*>(u), static_cast<bf16_t*>(q), kv, sl.reqs, sl.row_req, page_tables};
+    hipLaunchKernelGGL(gemm_bf16_mfma<FrontEpilogue<bf16_t>>, dim3((sl.N + 127) / 128, 4 * hd.d / 64), dim3(256), 0,
+                       stream, static_cast<const uint16_t*>(xn), static_cast<const uint16_t*>(w1), sl.N, hd.d, epi);
+  } else {
+    FrontEpilogue<float> epi{hd, layer, b1, static_cast<float*>(u), static_cast<float*>(q), kv, sl.reqs, sl.row_req, page_tables};
+    const uint64_t total = static_cast<uint64_t>(sl.N) * 4 * hd.d;
+    hipLaunchKernelGGL(gemm_f32_simple<FrontEpilogue<float>>, dim3(static_cast<uint32_t>((total + 255) / 256)), dim3(256),
+                       0, stream, static_cast<const float*>(xn), static_cast<const float*>(w1), sl.N, hd.d, 4 * hd.d, epi);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_back(const HstuDims& hd, const void* g, const void* w2, const float* b2, const void* x,
+                            void* y, uint32_t N, hipStream_t stream) {
+  if (N == 0) return hipSuccess;
+  if (hd.elem == 1) {
+    BackEpilogue<bf16_t> epi{hd.d, b2, static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y)};
+    hipLaunchKernelGGL(gemm_bf16_mfma<BackEpilogue<bf16_t>>, dim3((N + 127) / 128, hd.d / 64), dim3(256), 0, stream,
+                       static_cast<const uint16_t*>(g), static_cast<const uint16_t*>(w2), N, hd.d, epi);
+  } else {
+    BackEpilogue<float> epi{hd.d, b2, static_cast<const float*>(x), static_cast<float*>(y)};
+    const uint64_t total = static_cast<uint64_t>(N) * hd.d;
+    hipLaunchKernelGGL(gemm_f32_simple<BackEpilogue<float>>, dim3(static_cast<uint32_t>((total + 255) / 256)), dim3(256), 0,
+                       stream, static_cast<const float*>(g), static_cast<const float*>(w2), N, hd.d, hd.d, epi);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_attention(const HstuDims& hd, uint32_t layer, const void* q, const float* pos, const float* time,
+                            const KvView& kv, const StepLists& sl, const int32_t* page_tables, const int64_t* ts,
+                            void* o, hipStream_t stream) {
+  if (sl.N == 0) return hipSuccess;
+  if (hd.elem == 1) {
+    hipLaunchKernelGGL(attention_bf16_mfma, dim3(sl.n_tiles, hd.H), dim3(256), 0, stream, hd, layer,
+                       static_cast<const uint16_t*>(q), pos, time, kv, sl.reqs, sl.tiles, page_tables,
+                       reinterpret_cast<const long long*>(ts), static_cast<uint16_t*>(o));
+  } else {
+    const uint32_t items = sl.N * hd.H;
+    hipLaunchKernelGGL(attention_f32, dim3((items + 3) / 4), dim3(256), 0, stream, hd, layer,
+                       static_cast<const float*>(q), pos, time, kv, sl.reqs, sl.row_req, sl.N, page_tables,
+                       reinterpret_cast<const long long*>(ts), static_cast<float*>(o));
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose_weights(const void* w, void* wt, uint32_t rows, uint32_t cols, uint32_t elem,
+                                    hipStream_t stream) {
+  const dim3 grid((cols + 31) / 32, (rows + 31) / 32), block(32, 8);
+  if (elem == 1)
+    hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, block, 0, stream, static_cast<const uint16_t*>(w),
+                       static_cast<uint16_t*>(wt), rows, cols);
+  else
+    hipLaunchKernelGGL(transpose_kernel<float>, grid, block, 0, stream, static_cast<const float*>(w),
+                       static_cast<float*>(wt), rows, cols);
+  return hipGetLastError();
+}
+
+}  // namespace racer

@@ -1,0 +1,109 @@
+// Launch interfaces between the C-ABI layer and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace racer {
+
+// Device counters (unsigned long long each)
+enum Counter : int {
+  kCtrLookups = 0, kCtrHits, kCtrMisses, kCtrUnique, kCtrInserted, kCtrEvicted, kCtrBypassed,
+  kCtrInvalid, kCtrShrinkEvicted, kCtrShrinkMoved, kCtrBadPages, kCtrCount
+};
+
+// Everything a kernel needs to find a cache set, its ways and its rows.
+// Way layer w of the cache = slot w of every set = `layer_pages` consecutive logical EMB
+// pages; slot (w, s) lives in logical page w*layer_pages + s/spp at offset s%spp.
+struct EmbView {
+  uint8_t* base;            // pool backing store
+  uint64_t page_size;
+  uint32_t row_bytes;
+  uint32_t spp;             // slots per page
+  uint32_t w_max;
+  uint32_t elem;            // 0 fp32, 1 bf16
+  uint32_t sets;
+  uint32_t layer_pages;
+  uint32_t full_ways;       // n_emb / layer_pages
+  uint32_t part_sets;       // (n_emb % layer_pages) * spp: these sets have one more way
+  uint32_t* tags;           // [sets][w_max]
+  uint32_t* stamps;         // [sets][w_max]
+  const int32_t* emb_pages; // logical -> physical page
+  const uint8_t* table;     // device-visible address of the pinned host table
+  uint64_t rows;
+  unsigned long long* counters;
+};
+
+// Per-call scratch of the miss path.  ctr points at three zeroed words:
+// [0] misses listed, [1] deferred output rows, [2] unique misses.
+struct MissWs {
+  uint32_t* ctr;
+  uint32_t* ctr_next;       // the other parity's words, zeroed by the probe kernel
+  uint32_t* miss_list;      // lookup indices that missed
+  uint32_t* def_list;       // output rows that wait for a miss
+  int64_t* loc;             // per lookup of a deferred row: >=0 pool byte offset, -1 zero row, <=-3 staging row -(v+3)
+  unsigned long long* hkeys;  // id dedupe table: (batch << 32) | id
+  unsigned long long* hvals;  // (batch << 32) | (0xFFFFFFFF - first lookup index)
+  uint32_t* hslot_u;          // unique-miss number of the table slot
+  uint32_t hmask;
+  unsigned long long* heads;  // per-set chains of unique misses: (batch << 32) | unique number
+  uint32_t headmask;
+  uint32_t* u_i;
+  uint32_t* u_id;
+  uint32_t* u_set;
+  int32_t* u_next;
+  int32_t* u_way;
+  uint8_t* staging;         // [unique][row_bytes] rows fetched from the host table
+};
+
+hipError_t launch_emb_lookup(const EmbView& v, const MissWs& ws, const int64_t* ids, uint32_t n,
+                             uint32_t bag, uint8_t* out, uint8_t* hit_flags, uint32_t batch,
+                             hipStream_t stream);
+
+hipError_t launch_emb_shrink(const EmbView& v, uint32_t old_full, uint32_t old_part_sets,
+                             hipStream_t stream);
+
+hipError_t launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t stream);
+
+// ---- HSTU -----------------------------------------------------------------------------
+struct HstuDims {
+  uint32_t L, d, H, dh, elem, pt, n_pos, n_time;
+  float inv_n, eps;
+};
+
+struct ReqDev {  // device copy of one request
+  uint32_t prefix_len, new_len;
+  uint32_t page_table_off, ts_off, x_off, pad;
+};
+
+struct KvView {
+  uint8_t* base;
+  uint64_t page_size;
+  uint32_t n_pages;
+  unsigned long long* counters;
+};
+
+// row -> request map and work list built on the host for one step
+struct StepLists {
+  const ReqDev* reqs;        // [B]
+  const uint32_t* row_req;   // [N] request of each new-token row
+  const uint32_t* tiles;     // attention work items, longest first: (req << 16 | q_tile) pairs as 2 words
+  uint32_t n_tiles;
+  uint32_t B, N;
+};
+
+hipError_t launch_layernorm(const HstuDims& hd, const void* x, const float* g, const float* b,
+                            const void* gate /*nullable: multiply by gate rows*/, void* y, uint32_t N,
+                            hipStream_t stream);
+hipError_t launch_gemm_front(const HstuDims& hd, uint32_t layer, const void* xn, const void* w1t,
+                             const float* b1, void* u, void* q, const KvView& kv, const StepLists& sl,
+                             const int32_t* page_tables, hipStream_t stream);
+hipError_t launch_gemm_back(const HstuDims& hd, const void* g, const void* w2t, const float* b2,
+                            const void* x, void* y, uint32_t N, hipStream_t stream);
+hipError_t launch_attention(const HstuDims& hd, uint32_t layer, const void* q, const float* pos,
+                            const float* time, const KvView& kv, const StepLists& sl,
+                            const int32_t* page_tables, const int64_t* ts, void* o, hipStream_t stream);
+hipError_t launch_transpose_weights(const void* w, void* wt, uint32_t rows, uint32_t cols, uint32_t elem,
+                                    hipStream_t stream);
+
+}  // namespace racer

@@ -1,0 +1,588 @@
+// C-ABI layer: argument checks, host bookkeeping, workspaces, kernel launches.
+// Declarations and their semantics are in include/racer_pool.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/racer_pool.h"
+#include "kernels.h"
+#include "pool_host.h"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int32_t hip_fail(hipError_t e, const char* what) {
+  g_last_error = std::string(what) + ": " + hipGetErrorString(e);
+  return RACER_EHIP;
+}
+
+#define HIP_TRY(expr)                                   \
+  do {                                                  \
+    hipError_t _e = (expr);                             \
+    if (_e != hipSuccess) return hip_fail(_e, #expr);   \
+  } while (0)
+
+bool is_pow2(uint64_t x) { return x && !(x & (x - 1)); }
+
+template <typename T>
+int32_t dev_alloc(T** p, uint64_t count, bool zero) {
+  *p = nullptr;
+  if (count == 0) count = 1;
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(p), count * sizeof(T)));
+  if (zero) HIP_TRY(hipMemset(*p, 0, count * sizeof(T)));
+  return RACER_OK;
+}
+
+// Pinned staging that is written by the host and copied to the device asynchronously;
+// two buffers alternate so a call only ever waits for the copy issued two calls earlier.
+struct Staging {
+  uint8_t* buf[2] = {nullptr, nullptr};
+  hipEvent_t done[2] = {nullptr, nullptr};
+  uint64_t cap[2] = {0, 0};
+  bool pending[2] = {false, false};
+  int next = 0;
+
+  int32_t acquire(uint64_t bytes, uint8_t** out, int* which) {
+    const int k = next;
+    next ^= 1;
+    if (pending[k]) {
+      HIP_TRY(hipEventSynchronize(done[k]));
+      pending[k] = false;
+    }
+    if (cap[k] < bytes) {
+      if (buf[k]) HIP_TRY(hipHostFree(buf[k]));
+      buf[k] = nullptr;
+      cap[k] = 0;
+      const uint64_t want = std::max<uint64_t>(bytes * 2, 1 << 16);
+      HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&buf[k]), want, hipHostMallocDefault));
+      cap[k] = want;
+    }
+    if (!done[k]) HIP_TRY(hipEventCreateWithFlags(&done[k], hipEventDisableTiming));
+    *out = buf[k];
+    *which = k;
+    return RACER_OK;
+  }
+  int32_t mark(int which, hipStream_t s) {
+    HIP_TRY(hipEventRecord(done[which], s));
+    pending[which] = true;
+    return RACER_OK;
+  }
+  void release() {
+    for (int k = 0; k < 2; ++k) {
+      if (pending[k]) (void)hipEventSynchronize(done[k]);
+      if (buf[k]) (void)hipHostFree(buf[k]);
+      if (done[k]) (void)hipEventDestroy(done[k]);
+      buf[k] = nullptr;
+      done[k] = nullptr;
+      pending[k] = false;
+      cap[k] = 0;
+    }
+  }
+};
+
+}  // namespace
+
+struct racer_pool {
+  racer::HostPool host;
+  racer_pool_cfg cfg;
+  uint8_t* base = nullptr;
+  uint64_t bytes = 0, page_size = 0;
+  bool device = false;
+  uint32_t* d_tags = nullptr;
+  uint32_t* d_stamps = nullptr;
+  int32_t* d_emb_pages = nullptr;
+  unsigned long long* d_counters = nullptr;
+  const uint8_t* d_table = nullptr;
+  Staging stage;
+  uint32_t batch = 0;
+  uint64_t launches = 0;  // emb_lookup calls that reached the device (selects the list-counter parity)
+  hipStream_t last_stream = nullptr;
+  // miss-path workspace, grown on demand
+  uint64_t ws_cap = 0;
+  uint32_t* ws_ctr = nullptr;
+  racer::MissWs ws{};
+  // hstu workspace
+  uint64_t hw_rows = 0, hw_d = 0, hw_esize = 0;
+  uint8_t* hw_buf = nullptr;
+  uint64_t hl_cap = 0;
+  uint8_t* hl_dev = nullptr;
+  Staging hstage;
+
+  racer_pool(uint64_t n_pages, const racer_pool_cfg& c, uint32_t spp) : host(n_pages, c.page_tokens, spp, c.w_max), cfg(c) {}
+
+  racer::EmbView view() const {
+    racer::EmbView v{};
+    v.base = base;
+    v.page_size = page_size;
+    v.row_bytes = cfg.row_bytes;
+    v.spp = host.spp();
+    v.w_max = cfg.w_max;
+    v.elem = cfg.elem;
+    v.sets = static_cast<uint32_t>(host.sets());
+    v.layer_pages = static_cast<uint32_t>(host.layer_pages());
+    v.full_ways = static_cast<uint32_t>(host.n_emb() / host.layer_pages());
+    v.part_sets = static_cast<uint32_t>((host.n_emb() % host.layer_pages()) * host.spp());
+    v.tags = d_tags;
+    v.stamps = d_stamps;
+    v.emb_pages = d_emb_pages;
+    v.table = d_table;
+    v.rows = cfg.rows;
+    v.counters = d_counters;
+    return v;
+  }
+};
+
+struct racer_hstu {
+  racer_hstu_cfg cfg;
+  racer_hstu_weights w;
+  void* w1t = nullptr;  // bf16 models: [L][4d][d], the MFMA kernels want output-major weights
+  void* w2t = nullptr;  // [L][d][d]
+};
+
+namespace {
+
+void free_miss_ws(racer_pool* p) {
+  racer::MissWs& w = p->ws;
+  (void)hipFree(p->ws_ctr);
+  (void)hipFree(w.miss_list); (void)hipFree(w.def_list); (void)hipFree(w.loc); (void)hipFree(w.hkeys); (void)hipFree(w.hvals);
+  (void)hipFree(w.hslot_u); (void)hipFree(w.heads); (void)hipFree(w.u_i); (void)hipFree(w.u_id); (void)hipFree(w.u_set);
+  (void)hipFree(w.u_next); (void)hipFree(w.u_way); (void)hipFree(w.staging);
+  p->ws = racer::MissWs{};
+  p->ws_ctr = nullptr;
+  p->ws_cap = 0;
+}
+
+int32_t ensure_miss_ws(racer_pool* p, uint64_t n) {
+  if (n <= p->ws_cap) return RACER_OK;
+  if (p->ws_cap) {
+    HIP_TRY(hipStreamSynchronize(p->last_stream));
+    free_miss_ws(p);
+  }
+  const uint64_t cap = std::max<uint64_t>(n, 1024);
+  uint64_t hsize = 2048;
+  while (hsize < 2 * cap) hsize <<= 1;
+  racer::MissWs& w = p->ws;
+  int32_t rc;
+  if ((rc = dev_alloc(&p->ws_ctr, 8, true))) return rc;
+  if ((rc = dev_alloc(&w.miss_list, cap, false))) return rc;
+  if ((rc = dev_alloc(&w.def_list, cap, false))) return rc;
+  if ((rc = dev_alloc(&w.loc, cap, false))) return rc;
+  if ((rc = dev_alloc(&w.hkeys, hsize, true))) return rc;
+  if ((rc = dev_alloc(&w.hvals, hsize, true))) return rc;
+  if ((rc = dev_alloc(&w.hslot_u, hsize, false))) return rc;
+  if ((rc = dev_alloc(&w.heads, hsize, true))) return rc;
+  if ((rc = dev_alloc(&w.u_i, cap, false))) return rc;
+  if ((rc = dev_alloc(&w.u_id, cap, false))) return rc;
+  if ((rc = dev_alloc(&w.u_set, cap, false))) return rc;
+  if ((rc = dev_alloc(&w.u_next, cap, false))) return rc;
+  if ((rc = dev_alloc(&w.u_way, cap, false))) return rc;
+  if ((rc = dev_alloc(&w.staging, cap * p->cfg.row_bytes, false))) return rc;
+  w.hmask = static_cast<uint32_t>(hsize - 1);
+  w.headmask = static_cast<uint32_t>(hsize - 1);
+  p->ws_cap = cap;
+  return RACER_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* racer_last_error(void) { return g_last_error.c_str(); }
+
+int32_t pool_create(void* dev_base, uint64_t bytes, uint64_t page_size, const racer_pool_cfg* cfg, racer_pool_t** out) {
+  if (!cfg || !out) return RACER_EINVAL;
+  *out = nullptr;
+  if (cfg->row_bytes == 0 || cfg->row_bytes % 16 != 0) return RACER_EINVAL;
+  if (cfg->elem != RACER_ELEM_F32 && cfg->elem != RACER_ELEM_BF16) return RACER_EINVAL;
+  if (cfg->page_tokens == 0 || !is_pow2(cfg->w_max) || cfg->w_max > 32) return RACER_EINVAL;
+  if (page_size == 0 || bytes == 0 || bytes % page_size != 0 || page_size % cfg->row_bytes != 0) return RACER_EINVAL;
+  const uint64_t n_pages = bytes / page_size;
+  if (n_pages % cfg->w_max != 0 || n_pages >= (1ull << 31)) return RACER_EINVAL;
+  if (cfg->rows >= 0xFFFFFFFFull) return RACER_EINVAL;
+  if (!(cfg->emb_frac0 >= 0.0 && cfg->emb_frac0 <= 1.0)) return RACER_EINVAL;
+  const uint64_t spp = page_size / cfg->row_bytes;
+  const uint64_t sets = n_pages / cfg->w_max * spp;
+  if (spp >= (1ull << 31) || sets >= (1ull << 32)) return RACER_EINVAL;
+  if (dev_base && (reinterpret_cast<uintptr_t>(dev_base) & 255)) return RACER_EINVAL;
+
+  racer_pool* p = new (std::nothrow) racer_pool(n_pages, *cfg, static_cast<uint32_t>(spp));
+  if (!p) return RACER_ENOMEM;
+  p->base = static_cast<uint8_t*>(dev_base);
+  p->bytes = bytes;
+  p->page_size = page_size;
+  p->device = dev_base != nullptr;
+  p->host.seed_emb(static_cast<uint64_t>(std::llround(cfg->emb_frac0 * static_cast<double>(n_pages))));
+  if (p->device) {
+    int32_t rc = RACER_OK;
+    const uint64_t n_tags = sets * cfg->w_max;
+    if ((rc = dev_alloc(&p->d_tags, n_tags, false)) || (rc = dev_alloc(&p->d_stamps, n_tags, true)) ||
+        (rc = dev_alloc(&p->d_emb_pages, n_pages, true)) ||
+        (rc = dev_alloc(&p->d_counters, racer::kCtrCount, true))) {
+      pool_destroy(p);
+      return rc;
+    }
+    hipError_t e = racer::launch_fill_u32(p->d_tags, n_tags, RACER_TAG_EMPTY, nullptr);
+    if (e == hipSuccess && p->host.n_emb())
+      e = hipMemcpy(p->d_emb_pages, p->host.emb_pages().data(), p->host.n_emb() * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e == hipSuccess && cfg->host_table) {
+      void* dp = nullptr;
+      e = hipHostGetDevicePointer(&dp, const_cast<void*>(cfg->host_table), 0);
+      p->d_table = static_cast<const uint8_t*>(dp);
+    }
+    if (e != hipSuccess) {
+      pool_destroy(p);
+      return hip_fail(e, "pool_create device setup");
+    }
+  }
+  *out = p;
+  return RACER_OK;
+}
+
+int32_t pool_destroy(racer_pool_t* p) {
+  if (!p) return RACER_EINVAL;
+  if (p->device) {
+    (void)hipStreamSynchronize(p->last_stream);
+    free_miss_ws(p);
+    p->stage.release();
+    p->hstage.release();
+    (void)hipFree(p->d_tags);
+    (void)hipFree(p->d_stamps);
+    (void)hipFree(p->d_emb_pages);
+    (void)hipFree(p->d_counters);
+    (void)hipFree(p->hw_buf);
+    (void)hipFree(p->hl_dev);
+  }
+  delete p;
+  return RACER_OK;
+}
+
+int32_t pool_set_split(racer_pool_t* p, double emb_frac, void* stream_v, double* achieved) {
+  if (!p) return RACER_EINVAL;
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  const uint64_t G = p->host.layer_pages();
+  const racer::SplitPlan plan = p->host.set_split(emb_frac);
+  if (plan.rc < 0) return plan.rc;
+  if (achieved) *achieved = static_cast<double>(p->host.n_emb()) / static_cast<double>(p->host.n_pages());
+  if (p->device && plan.new_emb != plan.old_emb) {
+    p->last_stream = stream;
+    if (plan.new_emb > plan.old_emb) {
+      // newly mapped logical pages: ship their physical ids; the new ways are already empty
+      const uint64_t count = plan.new_emb - plan.old_emb;
+      uint8_t* buf;
+      int which;
+      int32_t rc = p->stage.acquire(count * sizeof(int32_t), &buf, &which);
+      if (rc) return rc;
+      std::memcpy(buf, p->host.emb_pages().data() + plan.old_emb, count * sizeof(int32_t));
+      HIP_TRY(hipMemcpyAsync(p->d_emb_pages + plan.old_emb, buf, count * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+      if ((rc = p->stage.mark(which, stream))) return rc;
+    } else {
+      const uint32_t old_full = static_cast<uint32_t>(plan.old_emb / G);
+      const uint32_t old_part = static_cast<uint32_t>((plan.old_emb % G) * p->host.spp());
+      HIP_TRY(racer::launch_emb_shrink(p->view(), old_full, old_part, stream));
+    }
+  }
+  return plan.rc;
+}
+
+int32_t pool_stats(racer_pool_t* p, racer_pool_stats* out) {
+  if (!p || !out) return RACER_EINVAL;
+  std::memset(out, 0, sizeof(*out));
+  if (p->device) {
+    HIP_TRY(hipStreamSynchronize(p->last_stream));
+    unsigned long long c[racer::kCtrCount];
+    HIP_TRY(hipMemcpy(c, p->d_counters, sizeof(c), hipMemcpyDeviceToHost));
+    out->lookups = c[racer::kCtrLookups];
+    out->hits = c[racer::kCtrHits];
+    out->misses = c[racer::kCtrMisses];
+    out->unique_misses = c[racer::kCtrUnique];
+    out->inserted = c[racer::kCtrInserted];
+    out->evicted = c[racer::kCtrEvicted];
+    out->bypassed = c[racer::kCtrBypassed];
+    out->invalid_ids = c[racer::kCtrInvalid];
+    out->shrink_evicted = c[racer::kCtrShrinkEvicted];
+    out->shrink_moved = c[racer::kCtrShrinkMoved];
+    out->bad_pages = c[racer::kCtrBadPages];
+  }
+  out->pages_total = p->host.n_pages();
+  out->pages_emb = p->host.n_emb();
+  out->pages_kv_free = p->host.free_count();
+  out->pages_kv_used = p->host.n_pages() - p->host.n_emb() - p->host.free_count();
+  out->seqs_resident = p->host.seqs_resident();
+  out->seqs_evicted = p->host.seqs_evicted();
+  out->batch = p->batch;
+  return RACER_OK;
+}
+
+int32_t pool_dump(racer_pool_t* p, int64_t* emb_pages, uint8_t* owner) {
+  if (!p) return RACER_EINVAL;
+  if (emb_pages)
+    for (uint64_t k = 0; k < p->host.n_emb(); ++k) emb_pages[k] = p->host.emb_pages()[k];
+  if (owner) std::memcpy(owner, p->host.owner().data(), p->host.n_pages());
+  return RACER_OK;
+}
+
+int32_t emb_cache_dump(racer_pool_t* p, uint32_t* tags, uint32_t* stamps) {
+  if (!p || !p->device) return RACER_EINVAL;
+  HIP_TRY(hipStreamSynchronize(p->last_stream));
+  const uint64_t bytes = p->host.sets() * p->cfg.w_max * sizeof(uint32_t);
+  if (tags) HIP_TRY(hipMemcpy(tags, p->d_tags, bytes, hipMemcpyDeviceToHost));
+  if (stamps) HIP_TRY(hipMemcpy(stamps, p->d_stamps, bytes, hipMemcpyDeviceToHost));
+  return RACER_OK;
+}
+
+uint64_t pool_num_sets(const racer_pool_t* p) { return p ? p->host.sets() : 0; }
+
+int64_t pool_slot_of(const racer_pool_t* p, uint64_t set, uint32_t way) { return p ? p->host.slot_of(set, way) : -1; }
+
+int32_t kv_seq_reserve(racer_pool_t* p, uint64_t key, uint32_t tokens, int32_t* pages_out, uint32_t cap, uint32_t* n_out) {
+  return p ? p->host.reserve(key, tokens, pages_out, cap, n_out) : RACER_EINVAL;
+}
+int32_t kv_seq_lookup(const racer_pool_t* p, uint64_t key, uint32_t* tokens, int32_t* pages_out, uint32_t cap, uint32_t* n_out) {
+  return p ? p->host.lookup(key, tokens, pages_out, cap, n_out) : RACER_EINVAL;
+}
+int32_t kv_seq_pin(racer_pool_t* p, uint64_t key) { return p ? p->host.pin(key) : RACER_EINVAL; }
+int32_t kv_seq_unpin(racer_pool_t* p, uint64_t key) { return p ? p->host.unpin(key) : RACER_EINVAL; }
+int32_t kv_seq_release(racer_pool_t* p, uint64_t key) { return p ? p->host.release(key) : RACER_EINVAL; }
+
+int32_t emb_lookup(racer_pool_t* p, const int64_t* ids, uint64_t n, uint32_t bag, void* out, uint8_t* hit_flags, void* stream_v) {
+  if (!p || !p->device || !p->d_table) return RACER_EINVAL;
+  if (bag == 0 || bag > 64 || n % bag != 0 || n >= 0xFFFFFFFFull) return RACER_EINVAL;
+  if (n && (!ids || !out)) return RACER_EINVAL;
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  p->batch += 1;  // one call = one LRU batch, empty or not
+  if (n == 0) return RACER_OK;
+  int32_t rc = ensure_miss_ws(p, n);
+  if (rc) return rc;
+  racer::MissWs ws = p->ws;
+  ws.ctr = p->ws_ctr + 4 * (p->launches & 1);
+  ws.ctr_next = p->ws_ctr + 4 * ((p->launches + 1) & 1);
+  p->launches += 1;
+  p->last_stream = stream;
+  HIP_TRY(racer::launch_emb_lookup(p->view(), ws, ids, static_cast<uint32_t>(n), bag, static_cast<uint8_t*>(out),
+                                   hit_flags, p->batch, stream));
+  return RACER_OK;
+}
+
+// ---- HSTU ---------------------------------------------------------------------------------
+
+int32_t hstu_model_create(const racer_hstu_cfg* cfg, const racer_hstu_weights* w, racer_hstu_t** out) {
+  if (!cfg || !w || !out) return RACER_EINVAL;
+  *out = nullptr;
+  if (cfg->L == 0 || cfg->H == 0 || cfg->d == 0 || cfg->d % cfg->H != 0) return RACER_EINVAL;
+  if (cfg->page_tokens == 0 || cfg->n_pos == 0 || cfg->n_time == 0 || cfg->n_time > 64) return RACER_EINVAL;
+  if (!(cfg->n_scale > 0.0f) || !(cfg->eps > 0.0f) || cfg->d > 1024) return RACER_EINVAL;
+  const uint32_t dh = cfg->d / cfg->H;
+  if (cfg->elem == RACER_ELEM_BF16) {
+    if (dh != 64 || cfg->d % 64 != 0 || cfg->page_tokens % 8 != 0) return RACER_EINVAL;
+  } else if (cfg->elem == RACER_ELEM_F32) {
+    if (dh > 64 || cfg->d % 16 != 0) return RACER_EINVAL;
+  } else {
+    return RACER_EINVAL;
+  }
+  const void* ptrs[] = {w->ln1_g, w->ln1_b, w->w1, w->b1, w->ln2_g, w->ln2_b, w->w2, w->b2, w->pos, w->time};
+  for (const void* q : ptrs)
+    if (!q) return RACER_EINVAL;
+  racer_hstu* m = new (std::nothrow) racer_hstu();
+  if (!m) return RACER_ENOMEM;
+  m->cfg = *cfg;
+  m->w = *w;
+  if (cfg->elem == RACER_ELEM_BF16) {
+    const uint64_t d = cfg->d;
+    hipError_t e = hipMalloc(&m->w1t, cfg->L * d * 4 * d * 2);
+    if (e == hipSuccess) e = hipMalloc(&m->w2t, cfg->L * d * d * 2);
+    for (uint32_t l = 0; l < cfg->L && e == hipSuccess; ++l) {
+      e = racer::launch_transpose_weights(static_cast<const uint16_t*>(w->w1) + l * d * 4 * d,
+                                          static_cast<uint16_t*>(m->w1t) + l * d * 4 * d, cfg->d, 4 * cfg->d, 1, nullptr);
+      if (e == hipSuccess)
+        e = racer::launch_transpose_weights(static_cast<const uint16_t*>(w->w2) + l * d * d,
+                                            static_cast<uint16_t*>(m->w2t) + l * d * d, cfg->d, cfg->d, 1, nullptr);
+    }
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+      hstu_model_destroy(m);
+      return hip_fail(e, "hstu_model_create weight transpose");
+    }
+  }
+  *out = m;
+  return RACER_OK;
+}
+
+int32_t hstu_model_destroy(racer_hstu_t* m) {
+  if (!m) return RACER_EINVAL;
+  (void)hipFree(m->w1t);
+  (void)hipFree(m->w2t);
+  delete m;
+  return RACER_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+struct StepCtx {
+  racer::HstuDims hd;
+  racer::KvView kv;
+  racer::StepLists sl;
+  uint64_t esize;
+};
+
+// Validate the requests, build the row->request map and the attention work list (largest
+// amount of key tiles first), ship them to the device on `stream`.
+int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, uint32_t B, uint64_t n_page_entries,
+                     hipStream_t stream, StepCtx* ctx) {
+  const racer_hstu_cfg& c = m->cfg;
+  if (!p->device || c.page_tokens != p->cfg.page_tokens || c.elem != p->cfg.elem) return RACER_EINVAL;
+  const uint64_t esize = c.elem == RACER_ELEM_BF16 ? 2 : 4;
+  if (static_cast<uint64_t>(c.page_tokens) * 2 * c.L * c.d * esize != p->page_size) return RACER_EINVAL;
+  uint64_t N = 0;
+  for (uint32_t r = 0; r < B; ++r) {
+    const racer_hstu_req& q = reqs[r];
+    const uint64_t S = static_cast<uint64_t>(q.prefix_len) + q.new_len;
+    const uint64_t need = (S + c.page_tokens - 1) / c.page_tokens;
+    if (q.page_table_off + need > n_page_entries) return RACER_EINVAL;
+    if (q.x_off != N) return RACER_EINVAL;  // rows are packed request after request
+    if (q.page_table_off >= (1ull << 32) || q.ts_off >= (1ull << 32) || S >= (1ull << 31)) return RACER_EINVAL;
+    N += q.new_len;
+  }
+  if (N >= (1ull << 31) || B >= (1u << 24)) return RACER_EINVAL;
+
+  struct Tile { uint32_t req, qt; uint64_t work; };
+  std::vector<Tile> tiles;
+  for (uint32_t r = 0; r < B; ++r) {
+    const uint32_t T = reqs[r].new_len;
+    for (uint32_t qt = 0; qt * 128 < T; ++qt) {
+      const uint64_t last = static_cast<uint64_t>(reqs[r].prefix_len) + std::min<uint64_t>(qt * 128 + 127, T - 1);
+      tiles.push_back({r, qt, last / 64 + 1});
+    }
+  }
+  std::stable_sort(tiles.begin(), tiles.end(), [](const Tile& a, const Tile& b) { return a.work > b.work; });
+
+  const uint64_t bytes_reqs = sizeof(racer::ReqDev) * std::max<uint32_t>(B, 1);
+  const uint64_t bytes_rows = sizeof(uint32_t) * std::max<uint64_t>(N, 1);
+  const uint64_t bytes_tiles = sizeof(uint32_t) * 2 * std::max<size_t>(tiles.size(), 1);
+  const uint64_t off_rows = (bytes_reqs + 255) & ~255ull, off_tiles = (off_rows + bytes_rows + 255) & ~255ull;
+  const uint64_t total = off_tiles + bytes_tiles;
+  if (total > p->hl_cap) {
+    HIP_TRY(hipStreamSynchronize(p->last_stream));
+    if (p->hl_dev) HIP_TRY(hipFree(p->hl_dev));
+    p->hl_dev = nullptr;
+    p->hl_cap = 0;
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->hl_dev), total * 2));
+    p->hl_cap = total * 2;
+  }
+  uint8_t* hbuf;
+  int which;
+  int32_t rc = p->hstage.acquire(total, &hbuf, &which);
+  if (rc) return rc;
+  racer::ReqDev* hr = reinterpret_cast<racer::ReqDev*>(hbuf);
+  uint32_t* hrow = reinterpret_cast<uint32_t*>(hbuf + off_rows);
+  uint32_t* ht = reinterpret_cast<uint32_t*>(hbuf + off_tiles);
+  for (uint32_t r = 0; r < B; ++r) {
+    hr[r] = racer::ReqDev{reqs[r].prefix_len, reqs[r].new_len, static_cast<uint32_t>(reqs[r].page_table_off),
+                          static_cast<uint32_t>(reqs[r].ts_off), static_cast<uint32_t>(reqs[r].x_off), 0};
+    for (uint32_t i = 0; i < reqs[r].new_len; ++i) hrow[reqs[r].x_off + i] = r;
+  }
+  for (size_t k = 0; k < tiles.size(); ++k) {
+    ht[2 * k] = tiles[k].req;
+    ht[2 * k + 1] = tiles[k].qt;
+  }
+  HIP_TRY(hipMemcpyAsync(p->hl_dev, hbuf, total, hipMemcpyHostToDevice, stream));
+  if ((rc = p->hstage.mark(which, stream))) return rc;
+
+  ctx->esize = esize;
+  ctx->hd = racer::HstuDims{c.L, c.d, c.H, c.d / c.H, c.elem, c.page_tokens, c.n_pos, c.n_time, 1.0f / c.n_scale, c.eps};
+  ctx->kv = racer::KvView{p->base, p->page_size, static_cast<uint32_t>(p->host.n_pages()), p->d_counters};
+  ctx->sl.reqs = reinterpret_cast<const racer::ReqDev*>(p->hl_dev);
+  ctx->sl.row_req = reinterpret_cast<const uint32_t*>(p->hl_dev + off_rows);
+  ctx->sl.tiles = reinterpret_cast<const uint32_t*>(p->hl_dev + off_tiles);
+  ctx->sl.n_tiles = static_cast<uint32_t>(tiles.size());
+  ctx->sl.B = B;
+  ctx->sl.N = static_cast<uint32_t>(N);
+  return RACER_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, uint32_t B, const int32_t* page_tables,
+                  uint64_t n_page_entries, const void* x_in, const int64_t* ts, void* out, void* stream_v) {
+  if (!p || !m || (B && !reqs)) return RACER_EINVAL;
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  StepCtx ctx;
+  int32_t rc = prepare_step(p, m, reqs, B, n_page_entries, stream, &ctx);
+  if (rc) return rc;
+  p->last_stream = stream;
+  const uint32_t N = ctx.sl.N;
+  if (N == 0) return RACER_OK;
+  if (!page_tables || !x_in || !ts || !out) return RACER_EINVAL;
+  const racer_hstu_cfg& c = m->cfg;
+  const uint64_t d = c.d, mat = static_cast<uint64_t>(N) * d * ctx.esize;
+  const uint64_t slot = (mat + 255) & ~255ull;
+  if (p->hw_rows < N || p->hw_d != d || p->hw_esize != ctx.esize) {  // xn, u, q, o, two layer buffers
+    HIP_TRY(hipStreamSynchronize(stream));
+    if (p->hw_buf) HIP_TRY(hipFree(p->hw_buf));
+    p->hw_buf = nullptr;
+    p->hw_rows = 0;
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->hw_buf), slot * 6));
+    p->hw_rows = N;
+    p->hw_d = d;
+    p->hw_esize = ctx.esize;
+  }
+  const uint64_t stride = ((static_cast<uint64_t>(p->hw_rows) * d * ctx.esize) + 255) & ~255ull;
+  uint8_t* xn = p->hw_buf;
+  uint8_t* u = xn + stride;
+  uint8_t* q = u + stride;
+  uint8_t* o = q + stride;
+  uint8_t* xb[2] = {o + stride, o + 2 * stride};
+  const bool bf16 = c.elem == RACER_ELEM_BF16;
+  const uint64_t w1_layer = d * 4 * d * ctx.esize, w2_layer = d * d * ctx.esize;
+  const float* f = nullptr;
+  (void)f;
+  const void* x_cur = x_in;
+  for (uint32_t l = 0; l < c.L; ++l) {
+    void* x_next = (l + 1 == c.L) ? out : static_cast<void*>(xb[l & 1]);
+    const float* ln1_g = static_cast<const float*>(m->w.ln1_g) + l * d;
+    const float* ln1_b = static_cast<const float*>(m->w.ln1_b) + l * d;
+    const float* ln2_g = static_cast<const float*>(m->w.ln2_g) + l * d;
+    const float* ln2_b = static_cast<const float*>(m->w.ln2_b) + l * d;
+    const float* b1 = static_cast<const float*>(m->w.b1) + l * 4 * d;
+    const float* b2 = static_cast<const float*>(m->w.b2) + l * d;
+    const uint8_t* w1 = static_cast<const uint8_t*>(bf16 ? m->w1t : m->w.w1) + l * w1_layer;
+    const uint8_t* w2 = static_cast<const uint8_t*>(bf16 ? m->w2t : m->w.w2) + l * w2_layer;
+    HIP_TRY(racer::launch_layernorm(ctx.hd, x_cur, ln1_g, ln1_b, nullptr, xn, N, stream));
+    HIP_TRY(racer::launch_gemm_front(ctx.hd, l, xn, w1, b1, u, q, ctx.kv, ctx.sl, page_tables, stream));
+    HIP_TRY(racer::launch_attention(ctx.hd, l, q, static_cast<const float*>(m->w.pos), static_cast<const float*>(m->w.time),
+                                    ctx.kv, ctx.sl, page_tables, ts, o, stream));
+    HIP_TRY(racer::launch_layernorm(ctx.hd, o, ln2_g, ln2_b, u, xn, N, stream));
+    HIP_TRY(racer::launch_gemm_back(ctx.hd, xn, w2, b2, x_cur, x_next, N, stream));
+    x_cur = x_next;
+  }
+  return RACER_OK;
+}
+
+int32_t hstu_attn_paged(racer_pool_t* p, racer_hstu_t* m, uint32_t layer, const racer_hstu_req* reqs, uint32_t B,
+                        const int32_t* page_tables, uint64_t n_page_entries, const void* q, const int64_t* ts, void* o,
+                        void* stream_v) {
+  if (!p || !m || (B && !reqs) || layer >= m->cfg.L) return RACER_EINVAL;
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  StepCtx ctx;
+  int32_t rc = prepare_step(p, m, reqs, B, n_page_entries, stream, &ctx);
+  if (rc) return rc;
+  p->last_stream = stream;
+  if (ctx.sl.N == 0) return RACER_OK;
+  if (!page_tables || !q || !ts || !o) return RACER_EINVAL;
+  HIP_TRY(racer::launch_attention(ctx.hd, layer, q, static_cast<const float*>(m->w.pos), static_cast<const float*>(m->w.time),
+                                  ctx.kv, ctx.sl, page_tables, ts, o, stream));
+  return RACER_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,224 @@
+"""GPU parity of hstu_step / hstu_attn_paged against the fp64 oracle.
+
+Tolerance (row-wise relative error in the max norm, max_i|gpu_i - ref_i| / max_i|ref_i| per
+output row): 1e-4 for fp32 models, 2e-2 for bf16 models whose intermediates are rounded to
+bf16 while the oracle rounds only the stored K,V."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_04450_amd import binding as B
+from paper_2605_04450_amd import harness as Hn
+from paper_2605_04450_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {False: 1e-4, True: 2e-2}
+
+
+class Case:
+    """One model + pool on the device and the matching oracle state."""
+
+    def __init__(self, seed, L, d, H, pt, bf16, n_pos, n_time, n_scale, n_pages):
+        self.L, self.d, self.H, self.pt, self.bf16 = L, d, H, pt, bf16
+        self.rng = np.random.default_rng(seed)
+        self.elem = B.ELEM_BF16 if bf16 else B.ELEM_F32
+        self.w = synth.make_weights(self.rng, L, d, H, n_pos, n_time, bf16)
+        self.model = Hn.Model(L, d, H, self.elem, pt, n_pos, n_time, n_scale, self.w)
+        self.cfg = oracle.make_cfg(L, d, H, pt, n_pos, n_time, n_scale, 1e-6, bf16)
+        esz = 2 if bf16 else 4
+        self.n_pages = n_pages
+        self.pool = Hn.Pool(n_pages, self.model.page_size(), d * esz, self.elem, pt, 32, None, 0.25, zero_fill=False)
+        self.kv = np.zeros(n_pages * oracle.kv_elems_per_page(self.cfg), dtype=np.float32)
+        self.mem = self.pool.mem.view(torch.bfloat16 if bf16 else torch.float32)
+
+    def inputs(self, prefix, new, shuffle=True):
+        reqs, n_pt, n_ts, N = synth.make_requests(prefix, new, self.pt)
+        first_kv = self.n_pages // 4  # pages below are EMB
+        perm = first_kv + (self.rng.permutation(self.n_pages - first_kv) if shuffle else np.arange(self.n_pages - first_kv))
+        assert n_pt <= len(perm)
+        pts = perm[:n_pt].astype(np.int32)
+        ts = np.concatenate([synth.timestamps(self.rng, p + t) for p, t in zip(prefix, new)])
+        x = self.rng.standard_normal((N, self.d)).astype(np.float32)
+        if self.bf16:
+            x = synth.as_bf16_values(x)
+        return reqs, pts, ts, x
+
+    def run_gpu(self, reqs, pts, ts, x):
+        xd = torch.from_numpy(x).to(Hn.DEV).to(Hn.torch_dtype(self.elem))
+        out = torch.empty_like(xd)
+        rc = B.hstu_step(self.pool.h, self.model.h, reqs, torch.from_numpy(pts).to(Hn.DEV), xd,
+                         torch.from_numpy(ts).to(Hn.DEV), out)
+        assert rc == B.OK, (rc, B.last_error())
+        torch.cuda.synchronize()
+        return out.float().cpu().numpy()
+
+    def run_oracle(self, reqs, pts, ts, x):
+        rc, ref = oracle.hstu_step(self.cfg, self.w, reqs, pts, self.kv, x, ts)
+        assert rc == oracle.OK
+        return ref
+
+    def oracle_kv_rows(self, pages, S, layer):
+        """K, V [S][d] of one layer as the oracle stored them."""
+        dh = self.d // self.H
+        K = np.zeros((S, self.d), np.float32)
+        V = np.zeros((S, self.d), np.float32)
+        for j in range(S):
+            for h in range(self.H):
+                ko = oracle.kv_offset(self.cfg, int(pages[j // self.pt]), layer, 0, h, j % self.pt)
+                vo = oracle.kv_offset(self.cfg, int(pages[j // self.pt]), layer, 1, h, j % self.pt)
+                K[j, h * dh:(h + 1) * dh] = self.kv[ko:ko + dh]
+                V[j, h * dh:(h + 1) * dh] = self.kv[vo:vo + dh]
+        return K, V
+
+    def close(self):
+        self.model.close()
+        self.pool.close()
+
+
+def assert_close(got, ref, bf16, what=""):
+    err = Hn.rel_error_rows(got, ref)
+    assert np.isfinite(got).all(), what
+    assert err.max() <= TOL[bf16], (what, float(err.max()), int(err.argmax()))
+
+
+def test_tiny_config_fp32_full_output_and_stored_kv():
+    # Tiny config: 1 layer, d = 64, 2 heads, fp32, KV page 16 tokens, 4 requests x 256 tokens
+    c = Case(1, 1, 64, 2, 16, False, 256, 32, 256.0, 128)
+    reqs, pts, ts, x = c.inputs([0, 0, 0, 0], [256, 256, 256, 256])
+    got, ref = c.run_gpu(reqs, pts, ts, x), c.run_oracle(reqs, pts, ts, x)
+    assert_close(got, ref, False, "tiny")
+    for (P, T, pto, tso, xo) in reqs[:2]:
+        pages = pts[pto:pto + 16]
+        Kg, Vg = Hn.read_kv(c.mem, c.L, c.d, c.H, c.pt, pages, 256, 0)
+        Ko, Vo = c.oracle_kv_rows(pages, 256, 0)
+        assert np.allclose(Kg.cpu().numpy(), Ko, rtol=1e-4, atol=1e-6)
+        assert np.allclose(Vg.cpu().numpy(), Vo, rtol=1e-4, atol=1e-6)
+    assert c.pool.stats()["bad_pages"] == 0
+    c.close()
+
+
+@pytest.mark.parametrize("L,d,H,pt,lens", [
+    (2, 128, 2, 16, [130, 64, 257, 1, 33]),
+    (1, 256, 4, 64, [300, 129, 64]),
+    (3, 64, 1, 8, [70, 5]),
+])
+def test_bf16_prefill_ragged_lengths(L, d, H, pt, lens):
+    c = Case(2, L, d, H, pt, True, max(lens), 16, float(max(lens)), 256)
+    reqs, pts, ts, x = c.inputs([0] * len(lens), lens)
+    got, ref = c.run_gpu(reqs, pts, ts, x), c.run_oracle(reqs, pts, ts, x)
+    assert_close(got, ref, True, "bf16 prefill")
+    # stored K,V of the last layer agree with the oracle's to bf16 resolution
+    (P, T, pto, tso, xo) = reqs[0]
+    pages = pts[pto:pto + (T + pt - 1) // pt]
+    Kg, Vg = Hn.read_kv(c.mem, c.L, c.d, c.H, c.pt, pages, T, L - 1)
+    Ko, Vo = c.oracle_kv_rows(pages, T, L - 1)
+    assert np.abs(Kg.float().cpu().numpy() - Ko).max() <= 3e-2 * max(1.0, np.abs(Ko).max())
+    assert np.abs(Vg.float().cpu().numpy() - Vo).max() <= 3e-2 * max(1.0, np.abs(Vo).max())
+    assert c.pool.stats()["bad_pages"] == 0
+    c.close()
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_prefix_reuse_two_steps(bf16):
+    # step 1 prefills, step 2 scores new tokens against the cached prefix (KV reuse)
+    L, d, H, pt = (2, 128, 2, 16) if bf16 else (2, 64, 2, 16)
+    c = Case(3, L, d, H, pt, bf16, 512, 16, 512.0, 128)
+    first, more = [200, 77, 130], [60, 140, 1]
+    reqs1, pts, ts, x_all = c.inputs([0, 0, 0], [a + b for a, b in zip(first, more)])
+    # carve the two steps out of the same page tables / timestamps
+    def step_inputs(prefix, new, take_from):
+        reqs, rows = [], []
+        xo = 0
+        for r, (P_, T_, pto, tso, xoff) in enumerate(reqs1):
+            reqs.append((prefix[r], new[r], pto, tso, xo))
+            rows.append(x_all[xoff + take_from[r]: xoff + take_from[r] + new[r]])
+            xo += new[r]
+        return reqs, np.concatenate(rows)
+    ra, xa = step_inputs([0, 0, 0], first, [0, 0, 0])
+    rb, xb = step_inputs(first, more, first)
+    ga, oa = c.run_gpu(ra, pts, ts, xa), c.run_oracle(ra, pts, ts, xa)
+    gb, ob = c.run_gpu(rb, pts, ts, xb), c.run_oracle(rb, pts, ts, xb)
+    assert_close(ga, oa, bf16, "step 1")
+    assert_close(gb, ob, bf16, "step 2 on cached prefix")
+    c.close()
+
+
+@pytest.mark.parametrize("bf16,d,H,pt", [(True, 128, 2, 16), (True, 64, 1, 64), (False, 64, 2, 16), (False, 48, 3, 4)])
+def test_attention_alone_on_synthetic_cache(bf16, d, H, pt):
+    P, T = [300, 0, 65], [140, 129, 1]
+    c = Case(4, 1, d, H, pt, bf16, 256, 12, 300.0, 96)  # n_pos < sequence length: the clamp is used
+    reqs, pts, ts, x = c.inputs(P, T)
+    dh = d // H
+    rng = c.rng
+    q = rng.standard_normal((sum(T), d)).astype(np.float32)
+    if bf16:
+        q = synth.as_bf16_values(q)
+    dt = Hn.torch_dtype(c.elem)
+    for (P_, T_, pto, tso, xo) in reqs:
+        S = P_ + T_
+        pages = pts[pto:pto + (S + pt - 1) // pt]
+        k = (rng.standard_normal((S, d)) / np.sqrt(np.sqrt(dh))).astype(np.float32)
+        v = rng.standard_normal((S, d)).astype(np.float32)
+        if bf16:
+            k, v = synth.as_bf16_values(k), synth.as_bf16_values(v)
+        Hn.write_prefix_kv(c.mem, 1, d, H, pt, pages, torch.from_numpy(k).to(Hn.DEV).to(dt),
+                           torch.from_numpy(v).to(Hn.DEV).to(dt), 0)
+        for j in range(S):
+            for h in range(H):
+                ko = oracle.kv_offset(c.cfg, int(pages[j // pt]), 0, 0, h, j % pt)
+                vo = oracle.kv_offset(c.cfg, int(pages[j // pt]), 0, 1, h, j % pt)
+                c.kv[ko:ko + dh] = k[j, h * dh:(h + 1) * dh]
+                c.kv[vo:vo + dh] = v[j, h * dh:(h + 1) * dh]
+    qd = torch.from_numpy(q).to(Hn.DEV).to(dt)
+    o = torch.empty_like(qd)
+    rc = B.hstu_attn_paged(c.pool.h, c.model.h, 0, reqs, torch.from_numpy(pts).to(Hn.DEV), qd,
+                           torch.from_numpy(ts).to(Hn.DEV), o)
+    assert rc == B.OK, B.last_error()
+    torch.cuda.synchronize()
+    got = o.float().cpu().numpy()
+    for (P_, T_, pto, tso, xo) in reqs:
+        S = P_ + T_
+        ref = oracle.attn_paged(c.cfg, 0, c.w["pos"][0], c.w["time"][0], P_, T_, pts[pto:pto + (S + pt - 1) // pt],
+                                ts[tso:tso + S], c.kv, q[xo:xo + T_].astype(np.float64))
+        assert_close(got[xo:xo + T_], ref, bf16, "attention")
+    c.close()
+
+
+def test_outputs_do_not_depend_on_page_placement_or_page_size():
+    outs = []
+    for pt, shuffle in ((16, False), (16, True), (64, True)):
+        c = Case(5, 2, 128, 2, pt, True, 300, 16, 300.0, 128)
+        reqs, pts, ts, x = c.inputs([0, 0], [300, 100], shuffle=shuffle)
+        outs.append(c.run_gpu(reqs, pts, ts, x))
+        c.close()
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+def test_bad_page_ids_are_skipped_and_counted():
+    c = Case(6, 1, 64, 2, 16, False, 64, 8, 64.0, 64)
+    reqs, pts, ts, x = c.inputs([0], [40])
+    bad = pts.copy()
+    bad[1] = 10**6
+    out = c.run_gpu(reqs, bad, ts, x)
+    assert np.isfinite(out).all()
+    assert c.pool.stats()["bad_pages"] > 0
+    c.close()
+
+
+def test_shape_errors_are_reported():
+    c = Case(7, 1, 64, 2, 16, False, 64, 8, 64.0, 64)
+    reqs, pts, ts, x = c.inputs([0], [40])
+    xd = torch.from_numpy(x).to(Hn.DEV)
+    out = torch.empty_like(xd)
+    ptd, tsd = torch.from_numpy(pts).to(Hn.DEV), torch.from_numpy(ts).to(Hn.DEV)
+    assert B.hstu_step(c.pool.h, c.model.h, [(0, 40, 0, 0, 5)], ptd, xd, tsd, out) == B.EINVAL   # rows not packed
+    assert B.hstu_step(c.pool.h, c.model.h, [(0, 400, 0, 0, 0)], ptd, xd, tsd, out) == B.EINVAL  # table too short
+    w = synth.make_weights(c.rng, 1, 64, 2, 64, 8, False)
+    other = Hn.Model(1, 64, 2, B.ELEM_F32, 32, 64, 8, 64.0, w)  # different page size
+    assert B.hstu_step(c.pool.h, other.h, reqs, ptd, xd, tsd, out) == B.EINVAL
+    rc, h = B.hstu_model_create(1, 96, 2, B.ELEM_BF16, 16, 64, 8, 64.0, 1e-6, other.w)  # d_h = 48 in bf16
+    assert rc == B.EINVAL
+    other.close()
+    c.close()
