@@ -1,0 +1,213 @@
+"""Benchmark of one HSTU serving step (emb_lookup + hstu_step) on one MI355X.
+
+Default workload = the "Mid" configuration: 4 HSTU layers, d = 256, 4 heads, bf16; embedding
+table 10M x 256 bf16 in pinned host memory; 64 GiB HBM pool of 256 KiB pages (64 KV tokens)
+at EMB:KV = 0.5; batch of 64 requests with lognormal history lengths (mean 2048, max 8192);
+Zipf(1.0) ids; every request is prefilled through its page table (prefix 0).
+
+Prints ONE JSON line (see README/DESIGN for the fields).  `--config tiny` runs the small fp32
+configuration instead (used for quick checks).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+PEAK_HBM_GBS = 8000.0
+PEAK_BF16_TFLOPS = 2500.0
+
+CONFIGS = {
+    # name: L, d, H, bf16, rows, pool_bytes, page_tokens, alpha, batch, mean_len, min_len, max_len, zipf_s, bag
+    "mid": dict(index=1, L=4, d=256, H=4, bf16=True, rows=10_000_000, pool_bytes=64 << 30, pt=64, alpha=0.5,
+                batch=64, mean_len=2048, min_len=64, max_len=8192, zipf=1.0, n_time=32, warm_batches=20,
+                desc="Mid: 4 layers d=256 H=4 bf16, table 10Mx256 bf16 pinned host, 64 GiB pool @ EMB:KV=0.5, "
+                     "batch 64 lognormal(mean 2048, max 8192) histories, Zipf(1.0), KV page 64 tokens"),
+    "tiny": dict(index=0, L=1, d=64, H=2, bf16=False, rows=100_000, pool_bytes=4 << 20, pt=16, alpha=0.5,
+                 batch=4, mean_len=256, min_len=256, max_len=256, zipf=1.0, n_time=32, warm_batches=4,
+                 desc="Tiny: 1 layer d=64 H=2 fp32, table 100k x 64 fp32, 4 MiB pool, 4 x 256 tokens, KV page 16"),
+}
+
+
+def build_workload(c, torch, Hn, B, synth):
+    dev = Hn.DEV
+    L, d, H, bf16, pt = c["L"], c["d"], c["H"], c["bf16"], c["pt"]
+    esz = 2 if bf16 else 4
+    elem = B.ELEM_BF16 if bf16 else B.ELEM_F32
+    rng = synth.rng_for(c["index"])
+    # host table (pinned)
+    if bf16:
+        table = torch.empty((c["rows"], d), dtype=torch.int16, pin_memory=True)
+        synth.fill_table_bf16_torch(table, synth.SEED_BASE + c["index"], dev)
+        table_t = table.view(torch.bfloat16)
+    else:
+        table_np = synth.make_table(rng, c["rows"], d, bf16=False)
+        table_t = Hn.to_device_table(table_np)
+    torch.cuda.synchronize()
+    page_size = pt * 2 * L * d * esz
+    n_pages = c["pool_bytes"] // page_size
+    pool = Hn.Pool(n_pages, page_size, d * esz, elem, pt, 32, table_t, c["alpha"])
+    lens = synth.history_lengths(rng, c["batch"], c["mean_len"], c["min_len"], c["max_len"])
+    n_pos = c["max_len"]
+    w = synth.make_weights(rng, L, d, H, n_pos, c["n_time"], bf16)
+    model = Hn.Model(L, d, H, elem, pt, n_pos, c["n_time"], float(c["max_len"]), w)
+    reqs, n_pt, n_ts, N = synth.make_requests([0] * len(lens), lens, pt)
+    pages = []
+    for key, s in enumerate(lens):
+        rc, pg = B.kv_seq_reserve(pool.h, key, int(s))
+        assert rc == B.OK, rc
+        B.kv_seq_pin(pool.h, key)
+        pages.append(pg)
+    pts = np.concatenate(pages).astype(np.int32)
+    ts = np.concatenate([synth.timestamps(rng, int(s)) for s in lens])
+    id_sets = [synth.zipf_ids(rng, c["rows"], c["zipf"], N) for _ in range(4)]
+    wl = dict(pool=pool, model=model, table=table_t, lens=lens, reqs=reqs, N=N, weights=w,
+              pts=pts, ts=ts, id_sets=id_sets, n_pos=n_pos, elem=elem, esz=esz, page_size=page_size, n_pages=n_pages)
+    wl["pts_dev"] = torch.from_numpy(pts).to(dev)
+    wl["ts_dev"] = torch.from_numpy(ts).to(dev)
+    wl["ids_dev"] = [torch.from_numpy(a).to(dev) for a in id_sets]
+    wl["reqs_c"] = (B.make_reqs(reqs), len(reqs))
+    wl["x"] = torch.empty((N, d), dtype=Hn.torch_dtype(elem), device=dev)
+    wl["out"] = torch.empty((N, d), dtype=Hn.torch_dtype(elem), device=dev)
+    return wl
+
+
+def one_step(wl, k, B):
+    ids = wl["ids_dev"][k % len(wl["ids_dev"])]
+    rc = B.emb_lookup(wl["pool"].h, ids, wl["x"], 1, None)
+    assert rc == B.OK, (rc, B.last_error())
+    rc = B.hstu_step(wl["pool"].h, wl["model"].h, wl["reqs_c"], wl["pts_dev"], wl["x"], wl["ts_dev"], wl["out"])
+    assert rc == B.OK, (rc, B.last_error())
+
+
+def cpu_baseline(c, wl, synth, budget_tokens):
+    """Time the oracle on a bounded sample: the first requests (in batch order) whose new tokens add
+    up to about `budget_tokens`, served as their own small step (EMB lookup + all layers)."""
+    import oracle
+    L, d, H, pt, bf16 = c["L"], c["d"], c["H"], c["pt"], c["bf16"]
+    lens = [int(s) for s in wl["lens"]]
+    order = np.argsort(lens)  # shortest first keeps the sample inside the time budget with several requests
+    take, tot = [], 0
+    for r in order:
+        if tot + lens[r] > budget_tokens and take:
+            break
+        take.append(int(r))
+        tot += lens[r]
+    sub_lens = [lens[r] for r in take]
+    reqs, n_pt, n_ts, N = synth.make_requests([0] * len(take), sub_lens, pt)
+    pts = np.arange(n_pt, dtype=np.int32)
+    ts = np.concatenate([wl["ts"][wl["reqs"][r][3]: wl["reqs"][r][3] + lens[r]] for r in take])
+    ids = np.concatenate([wl["id_sets"][0][wl["reqs"][r][4]: wl["reqs"][r][4] + lens[r]] for r in take])
+    # the oracle's table: only the sampled rows are materialised (row -> dense index), same values
+    uniq, inv = np.unique(ids, return_inverse=True)
+    if bf16:
+        sub = np.zeros((len(uniq), d), dtype=np.uint16)
+        tab = wl["table"].view(dtype=__import__("torch").int16)
+        sub[:] = tab[__import__("torch").from_numpy(uniq)].numpy().view(np.uint16)
+        x_vals = synth.from_bf16_bits(sub)
+    else:
+        sub = wl["table"][__import__("torch").from_numpy(uniq)].numpy()
+        x_vals = sub
+    orc_pool = oracle.Pool((2 * len(uniq) // 1024 + 2) * 32, pt, 32, 32, 0.5)  # capacity >= the distinct rows
+    cfg = oracle.make_cfg(L, d, H, pt, wl["n_pos"], c["n_time"], float(c["max_len"]), 1e-6, bf16)
+    kv = np.zeros(n_pt * oracle.kv_elems_per_page(cfg), dtype=np.float32)
+    threads = oracle.max_threads()
+    t0 = time.perf_counter()
+    rc, xo, hit = orc_pool.emb_lookup(inv.astype(np.int64), sub)
+    x = synth.from_bf16_bits(xo) if bf16 else xo
+    rc, ref = oracle.hstu_step(cfg, wl["weights"], reqs, pts, kv, x, ts, threads=0)
+    dt = time.perf_counter() - t0
+    return {"value": N / dt, "unit": "tokens/s", "cores": min(threads, len(take)), "kind": "oracle",
+            "sample": "%d shortest requests of the batch (%d tokens), EMB lookup + all %d layers, %.1f s, "
+                      "OpenMP over requests (%d threads available)" % (len(take), N, L, dt, threads)}, take, ref
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="mid", choices=sorted(CONFIGS))
+    ap.add_argument("--cpu-tokens", type=int, default=None, help="token budget of the oracle sample")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (every figure is the one "
+              "GPU's throughput)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2605_04450_amd import binding as B
+    from paper_2605_04450_amd import harness as Hn
+    from paper_2605_04450_amd import synth
+
+    B.load()
+    c = CONFIGS[args.config]
+    wl = build_workload(c, torch, Hn, B, synth)
+    pool = wl["pool"]
+    # warm the EMB cache, then whole warm-up steps
+    for k in range(c["warm_batches"]):
+        B.emb_lookup(pool.h, wl["ids_dev"][k % 4], wl["x"], 1, None)
+    for k in range(args.warmup):
+        one_step(wl, k, B)
+    torch.cuda.synchronize()
+    st0 = pool.stats()
+    B.racer_prof_enable(pool.h, 1)
+    B.racer_prof_read(pool.h)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        one_step(wl, k, B)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = B.racer_prof_read(pool.h)
+    B.racer_prof_enable(pool.h, 0)
+    st1 = pool.stats()
+    ms_per_step = dt * 1e3 / args.steps
+    N, d, L, H = wl["N"], c["d"], c["L"], c["H"]
+    lens = wl["lens"].astype(np.float64)
+    pairs = float((lens * (lens + 1) / 2).sum())             # causal (query, key) pairs per layer
+    attn_flop = 4.0 * d * pairs                                # 2*d_h for QK^T + 2*d_h for PV, per head, H heads
+    attn_ms = prof["attention"][0] / max(prof["attention"][1], 1)
+    attn_tflops = attn_flop / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else 0.0
+    R = d * wl["esz"]
+    lookups = st1["lookups"] - st0["lookups"]
+    hits = st1["hits"] - st0["hits"]
+    ways = pool.stats()["pages_emb"] / (wl["n_pages"] / 32)
+    gather_bytes = N * (8 + 4 * ways + 4 + R + R)             # id + tag line + stamp + row read + row write
+    gather_ms = prof["emb_gather"][0] / max(prof["emb_gather"][1], 1)
+    gather_gbs = gather_bytes / (gather_ms * 1e-3) / 1e9 if gather_ms > 0 else 0.0
+    kernels = {k: {"ms_per_launch": (v[0] / v[1] if v[1] else 0.0), "launches_per_step": v[1] / args.steps}
+               for k, v in prof.items()}
+    result = {
+        "metric": "hstu_step_tokens_per_s", "value": N / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if c["bf16"] else "f32", "data": "synthetic",
+        "config": {"workload": c["desc"], "new_tokens_per_step": int(N), "requests": int(c["batch"]),
+                   "emb_frac": c["alpha"], "causal_pairs_per_layer": pairs},
+        "emb_gather": {"GBps": gather_gbs, "frac_of_hbm_peak": gather_gbs / PEAK_HBM_GBS,
+                       "bytes_per_launch": gather_bytes, "ms_per_launch": gather_ms,
+                       "hit_rate": hits / max(lookups, 1)},
+        "roofline": {"kernel": "attention_bf16_mfma" if c["bf16"] else "attention_f32", "bound": "mfma",
+                     "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": attn_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "flop_per_launch": attn_flop, "ms_per_launch": attn_ms},
+        "kernels": kernels,
+    }
+    if not args.no_cpu:
+        budget = args.cpu_tokens or (1024 if args.config == "tiny" else 6000)
+        cb, take, ref = cpu_baseline(c, wl, synth, budget)
+        result["cpu_baseline"] = cb
+    print(json.dumps(result))
+    wl["model"].close()
+    pool.close()
+
+
+if __name__ == "__main__":
+    main()

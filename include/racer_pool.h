@@ -70,8 +70,11 @@ typedef struct {
  * pool_create: dev_base (dev, caller-owned, 256-byte aligned) backs bytes/page_size pages.
  * Requirements: bytes % page_size == 0, page_size % row_bytes == 0, pages % w_max == 0,
  * pages < 2^31.  Page p occupies [dev_base + p*page_size, +page_size).  On the KV side a
- * page holds page_tokens tokens of all layers ([layer][K|V][head][token][d_h]); on the EMB
- * side it holds page_size/row_bytes embedding slots.  round-half-away(emb_frac0 * pages)
+ * page holds page_tokens tokens of all layers as [layer][K|V][head] blocks of
+ * page_tokens*d_h elements: a K block is [token][d_h], a V block is stored transposed,
+ * [d_h][token] (the attention kernel contracts over tokens and reads them contiguously);
+ * KV bytes per token are 2*L*d*elem (paper Sec. V-E: 60-184 MB per user at 8K-15K tokens).
+ * On the EMB side a page holds page_size/row_bytes embedding slots.  round-half-away(emb_frac0 * pages)
  * lowest-numbered pages start on the EMB side, the rest on the KV free list.
  * dev_base == NULL creates a metadata-only pool (host bookkeeping works, device calls
  * return RACER_EINVAL): this is what CPU-only hosts can exercise.
@@ -188,6 +191,24 @@ int32_t hstu_attn_paged(racer_pool_t* pool, racer_hstu_t* model, uint32_t layer,
                         const racer_hstu_req* reqs, uint32_t B, const int32_t* kv_page_tables,
                         uint64_t n_page_entries, const void* q, const int64_t* ts, void* o,
                         void* stream);
+
+/* ---- per-kernel-class timing for benchmarks: when enabled, every launch (the miss path as
+ *      one group) is bracketed by HIP events on the caller's stream.  racer_prof_read waits
+ *      for the pool's last stream, adds up the intervals recorded since the previous read and
+ *      clears them. */
+#define RACER_PROF_EMB_GATHER 0 /* probe + hit gather kernel */
+#define RACER_PROF_EMB_MISS 1   /* the miss-path kernels of one emb_lookup, as a group */
+#define RACER_PROF_LAYERNORM 2
+#define RACER_PROF_GEMM_FRONT 3
+#define RACER_PROF_ATTENTION 4
+#define RACER_PROF_GEMM_BACK 5
+#define RACER_PROF_KINDS 6
+typedef struct {
+  double ms[RACER_PROF_KINDS];
+  uint64_t launches[RACER_PROF_KINDS];
+} racer_prof;
+int32_t racer_prof_enable(racer_pool_t* pool, int32_t on);
+int32_t racer_prof_read(racer_pool_t* pool, racer_prof* out);
 
 /* text of the last HIP error seen by this library on the calling thread ("" if none) */
 const char* racer_last_error(void);

@@ -20,8 +20,13 @@ EXPORTS = [
     "pool_create", "pool_destroy", "pool_set_split", "pool_stats", "pool_dump", "emb_cache_dump",
     "pool_num_sets", "pool_slot_of", "kv_seq_reserve", "kv_seq_lookup", "kv_seq_pin", "kv_seq_unpin",
     "kv_seq_release", "emb_lookup", "hstu_model_create", "hstu_model_destroy", "hstu_step",
-    "hstu_attn_paged", "racer_last_error",
+    "hstu_attn_paged", "racer_last_error", "racer_prof_enable", "racer_prof_read",
 ]
+PROF_KINDS = ("emb_gather", "emb_miss", "layernorm", "gemm_front", "attention", "gemm_back")
+
+
+class Prof(C.Structure):
+    _fields_ = [("ms", C.c_double * 6), ("launches", C.c_uint64 * 6)]
 
 
 class PoolCfg(C.Structure):
@@ -87,6 +92,8 @@ def load():
     L.hstu_model_destroy.argtypes = [vp]
     L.hstu_step.argtypes = [vp, vp, C.POINTER(HstuReq), u32, vp, u64, vp, vp, vp, vp]
     L.hstu_attn_paged.argtypes = [vp, vp, u32, C.POINTER(HstuReq), u32, vp, u64, vp, vp, vp, vp]
+    L.racer_prof_enable.argtypes = [vp, i32]
+    L.racer_prof_read.argtypes = [vp, C.POINTER(Prof)]
     L.racer_last_error.restype = C.c_char_p
     for name in EXPORTS:
         if name not in ("pool_num_sets", "pool_slot_of", "racer_last_error"):
@@ -97,6 +104,19 @@ def load():
 
 def last_error():
     return load().racer_last_error().decode()
+
+
+def racer_prof_enable(pool, on):
+    return load().racer_prof_enable(pool, int(on))
+
+
+def racer_prof_read(pool):
+    """{kind: (total ms, launches)} of the intervals recorded since the last read."""
+    pr = Prof()
+    rc = load().racer_prof_read(pool, C.byref(pr))
+    if rc != OK:
+        raise RuntimeError("racer_prof_read failed: %d %s" % (rc, last_error()))
+    return {k: (pr.ms[i], int(pr.launches[i])) for i, k in enumerate(PROF_KINDS)}
 
 
 def _dp(t):

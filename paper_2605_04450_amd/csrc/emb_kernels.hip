@@ -521,14 +521,19 @@ hipError_t launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t 
   return hipGetLastError();
 }
 
-hipError_t launch_emb_lookup(const EmbView& v, const MissWs& ws, const int64_t* ids, uint32_t n,
-                             uint32_t bag, uint8_t* out, uint8_t* hit_flags, uint32_t batch,
-                             hipStream_t stream) {
+hipError_t launch_emb_probe(const EmbView& v, const MissWs& ws, const int64_t* ids, uint32_t n, uint32_t bag,
+                            uint8_t* out, uint8_t* hit_flags, uint32_t batch, hipStream_t stream) {
   if (n == 0) return hipSuccess;
   const uint32_t lb = (64 / bag) * bag;
   const uint32_t per_block = 4 * lb;
   const uint32_t blocks = (n + per_block - 1) / per_block;
   hipLaunchKernelGGL(emb_probe_gather, dim3(blocks), dim3(256), 0, stream, v, ws, ids, n, bag, lb, out, hit_flags, batch);
+  return hipGetLastError();
+}
+
+hipError_t launch_emb_miss_path(const EmbView& v, const MissWs& ws, const int64_t* ids, uint32_t n, uint32_t bag,
+                                uint8_t* out, uint32_t batch, hipStream_t stream) {
+  if (n == 0) return hipSuccess;
   // the miss kernels size themselves from device counters; a modest grid keeps the
   // no-miss case cheap and still saturates PCIe when a cold batch arrives
   const uint32_t mblocks = n / 256 + 1 < 1024 ? n / 256 + 1 : 1024;

@@ -56,9 +56,10 @@ struct MissWs {
   uint8_t* staging;         // [unique][row_bytes] rows fetched from the host table
 };
 
-hipError_t launch_emb_lookup(const EmbView& v, const MissWs& ws, const int64_t* ids, uint32_t n,
-                             uint32_t bag, uint8_t* out, uint8_t* hit_flags, uint32_t batch,
-                             hipStream_t stream);
+hipError_t launch_emb_probe(const EmbView& v, const MissWs& ws, const int64_t* ids, uint32_t n, uint32_t bag,
+                            uint8_t* out, uint8_t* hit_flags, uint32_t batch, hipStream_t stream);
+hipError_t launch_emb_miss_path(const EmbView& v, const MissWs& ws, const int64_t* ids, uint32_t n, uint32_t bag,
+                                uint8_t* out, uint32_t batch, hipStream_t stream);
 
 hipError_t launch_emb_shrink(const EmbView& v, uint32_t old_full, uint32_t old_part_sets,
                              hipStream_t stream);

@@ -114,6 +114,11 @@ struct racer_pool {
   uint64_t hl_cap = 0;
   uint8_t* hl_dev = nullptr;
   Staging hstage;
+  // optional per-kernel-class timing with events on the caller's stream
+  struct ProfMark { hipEvent_t a, b; int kind; };
+  bool prof_on = false;
+  std::vector<ProfMark> prof;
+  std::vector<hipEvent_t> prof_spare;
 
   racer_pool(uint64_t n_pages, const racer_pool_cfg& c, uint32_t spp) : host(n_pages, c.page_tokens, spp, c.w_max), cfg(c) {}
 
@@ -147,6 +152,31 @@ struct racer_hstu {
 };
 
 namespace {
+
+// Bracket one launch (or a fixed group of launches) with events when timing is enabled.
+struct ProfScope {
+  racer_pool* p;
+  hipStream_t s;
+  bool live = false;
+  ProfScope(racer_pool* pool, int kind, hipStream_t stream) : p(pool), s(stream) {
+    if (!p->prof_on) return;
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    for (hipEvent_t& e : ev) {
+      if (!p->prof_spare.empty()) {
+        e = p->prof_spare.back();
+        p->prof_spare.pop_back();
+      } else if (hipEventCreate(&e) != hipSuccess) {
+        return;
+      }
+    }
+    if (hipEventRecord(ev[0], s) != hipSuccess) return;
+    p->prof.push_back({ev[0], ev[1], kind});
+    live = true;
+  }
+  ~ProfScope() {
+    if (live) (void)hipEventRecord(p->prof.back().b, s);
+  }
+};
 
 void free_miss_ws(racer_pool* p) {
   racer::MissWs& w = p->ws;
@@ -253,6 +283,11 @@ int32_t pool_destroy(racer_pool_t* p) {
     free_miss_ws(p);
     p->stage.release();
     p->hstage.release();
+    for (const racer_pool::ProfMark& m : p->prof) {
+      (void)hipEventDestroy(m.a);
+      (void)hipEventDestroy(m.b);
+    }
+    for (hipEvent_t e : p->prof_spare) (void)hipEventDestroy(e);
     (void)hipFree(p->d_tags);
     (void)hipFree(p->d_stamps);
     (void)hipFree(p->d_emb_pages);
@@ -366,8 +401,16 @@ int32_t emb_lookup(racer_pool_t* p, const int64_t* ids, uint64_t n, uint32_t bag
   ws.ctr_next = p->ws_ctr + 4 * ((p->launches + 1) & 1);
   p->launches += 1;
   p->last_stream = stream;
-  HIP_TRY(racer::launch_emb_lookup(p->view(), ws, ids, static_cast<uint32_t>(n), bag, static_cast<uint8_t*>(out),
-                                   hit_flags, p->batch, stream));
+  {
+    ProfScope t(p, RACER_PROF_EMB_GATHER, stream);
+    HIP_TRY(racer::launch_emb_probe(p->view(), ws, ids, static_cast<uint32_t>(n), bag, static_cast<uint8_t*>(out),
+                                    hit_flags, p->batch, stream));
+  }
+  {
+    ProfScope t(p, RACER_PROF_EMB_MISS, stream);
+    HIP_TRY(racer::launch_emb_miss_path(p->view(), ws, ids, static_cast<uint32_t>(n), bag, static_cast<uint8_t*>(out),
+                                        p->batch, stream));
+  }
   return RACER_OK;
 }
 
@@ -558,12 +601,27 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
     const float* b2 = static_cast<const float*>(m->w.b2) + l * d;
     const uint8_t* w1 = static_cast<const uint8_t*>(bf16 ? m->w1t : m->w.w1) + l * w1_layer;
     const uint8_t* w2 = static_cast<const uint8_t*>(bf16 ? m->w2t : m->w.w2) + l * w2_layer;
-    HIP_TRY(racer::launch_layernorm(ctx.hd, x_cur, ln1_g, ln1_b, nullptr, xn, N, stream));
-    HIP_TRY(racer::launch_gemm_front(ctx.hd, l, xn, w1, b1, u, q, ctx.kv, ctx.sl, page_tables, stream));
-    HIP_TRY(racer::launch_attention(ctx.hd, l, q, static_cast<const float*>(m->w.pos), static_cast<const float*>(m->w.time),
-                                    ctx.kv, ctx.sl, page_tables, ts, o, stream));
-    HIP_TRY(racer::launch_layernorm(ctx.hd, o, ln2_g, ln2_b, u, xn, N, stream));
-    HIP_TRY(racer::launch_gemm_back(ctx.hd, xn, w2, b2, x_cur, x_next, N, stream));
+    {
+      ProfScope t(p, RACER_PROF_LAYERNORM, stream);
+      HIP_TRY(racer::launch_layernorm(ctx.hd, x_cur, ln1_g, ln1_b, nullptr, xn, N, stream));
+    }
+    {
+      ProfScope t(p, RACER_PROF_GEMM_FRONT, stream);
+      HIP_TRY(racer::launch_gemm_front(ctx.hd, l, xn, w1, b1, u, q, ctx.kv, ctx.sl, page_tables, stream));
+    }
+    {
+      ProfScope t(p, RACER_PROF_ATTENTION, stream);
+      HIP_TRY(racer::launch_attention(ctx.hd, l, q, static_cast<const float*>(m->w.pos),
+                                      static_cast<const float*>(m->w.time), ctx.kv, ctx.sl, page_tables, ts, o, stream));
+    }
+    {
+      ProfScope t(p, RACER_PROF_LAYERNORM, stream);
+      HIP_TRY(racer::launch_layernorm(ctx.hd, o, ln2_g, ln2_b, u, xn, N, stream));
+    }
+    {
+      ProfScope t(p, RACER_PROF_GEMM_BACK, stream);
+      HIP_TRY(racer::launch_gemm_back(ctx.hd, xn, w2, b2, x_cur, x_next, N, stream));
+    }
     x_cur = x_next;
   }
   return RACER_OK;
@@ -580,8 +638,33 @@ int32_t hstu_attn_paged(racer_pool_t* p, racer_hstu_t* m, uint32_t layer, const 
   p->last_stream = stream;
   if (ctx.sl.N == 0) return RACER_OK;
   if (!page_tables || !q || !ts || !o) return RACER_EINVAL;
-  HIP_TRY(racer::launch_attention(ctx.hd, layer, q, static_cast<const float*>(m->w.pos), static_cast<const float*>(m->w.time),
-                                  ctx.kv, ctx.sl, page_tables, ts, o, stream));
+  {
+    ProfScope t(p, RACER_PROF_ATTENTION, stream);
+    HIP_TRY(racer::launch_attention(ctx.hd, layer, q, static_cast<const float*>(m->w.pos),
+                                    static_cast<const float*>(m->w.time), ctx.kv, ctx.sl, page_tables, ts, o, stream));
+  }
+  return RACER_OK;
+}
+
+int32_t racer_prof_enable(racer_pool_t* p, int32_t on) {
+  if (!p || !p->device) return RACER_EINVAL;
+  p->prof_on = on != 0;
+  return RACER_OK;
+}
+
+int32_t racer_prof_read(racer_pool_t* p, racer_prof* out) {
+  if (!p || !p->device || !out) return RACER_EINVAL;
+  std::memset(out, 0, sizeof(*out));
+  HIP_TRY(hipStreamSynchronize(p->last_stream));
+  for (const racer_pool::ProfMark& m : p->prof) {
+    float ms = 0.0f;
+    HIP_TRY(hipEventElapsedTime(&ms, m.a, m.b));
+    out->ms[m.kind] += ms;
+    out->launches[m.kind] += 1;
+    p->prof_spare.push_back(m.a);
+    p->prof_spare.push_back(m.b);
+  }
+  p->prof.clear();
   return RACER_OK;
 }
 

@@ -36,7 +36,8 @@ class Case:
     def inputs(self, prefix, new, shuffle=True):
         reqs, n_pt, n_ts, N = synth.make_requests(prefix, new, self.pt)
         first_kv = self.n_pages // 4  # pages below are EMB
-        perm = first_kv + (self.rng.permutation(self.n_pages - first_kv) if shuffle else np.arange(self.n_pages - first_kv))
+        perm_rng = np.random.default_rng(12345)  # its own stream: placement must not change the data drawn below
+        perm = first_kv + (perm_rng.permutation(self.n_pages - first_kv) if shuffle else np.arange(self.n_pages - first_kv))
         assert n_pt <= len(perm)
         pts = perm[:n_pt].astype(np.int32)
         ts = np.concatenate([synth.timestamps(self.rng, p + t) for p, t in zip(prefix, new)])
@@ -148,7 +149,7 @@ def test_prefix_reuse_two_steps(bf16):
 @pytest.mark.parametrize("bf16,d,H,pt", [(True, 128, 2, 16), (True, 64, 1, 64), (False, 64, 2, 16), (False, 48, 3, 4)])
 def test_attention_alone_on_synthetic_cache(bf16, d, H, pt):
     P, T = [300, 0, 65], [140, 129, 1]
-    c = Case(4, 1, d, H, pt, bf16, 256, 12, 300.0, 96)  # n_pos < sequence length: the clamp is used
+    c = Case(4, 1, d, H, pt, bf16, 256, 12, 300.0, 256)  # n_pos < sequence length: the clamp is used
     reqs, pts, ts, x = c.inputs(P, T)
     dh = d // H
     rng = c.rng
