@@ -107,7 +107,10 @@ struct FrontEpilogue {  // SiLU(acc + b1), split U | V | Q | K, K and V into the
     const float z = silu(acc + b1[col]);
     const uint32_t which = col / hd.d, c = col % hd.d;
     if (which == 0) { store_elem(u, static_cast<uint64_t>(row) * hd.d + c, z); return; }
-    if (which == 2) { store_elem(q, static_cast<uint64_t>(row) * hd.d + c, z); return; }
+    if (which == 2) {  // bf16 models: the attention kernel wants q * log2(e) (one rounding, here)
+      store_elem(q, static_cast<uint64_t>(row) * hd.d + c, sizeof(T) == 2 ? z * 1.4426950408889634f : z);
+      return;
+    }
     const ReqDev rq = reqs[row_req[row]];
     const uint32_t pos = rq.prefix_len + (row - rq.x_off);
     const int32_t page = page_tables[rq.page_table_off + pos / hd.pt];
@@ -267,19 +270,60 @@ __global__ __launch_bounds__(256) void attention_f32(HstuDims hd, uint32_t layer
 // registers, and feeds the bf16 result straight back as the second operand of
 // O^T += V^T P^T: the accumulator layout of the first product is exactly the operand layout
 // of the second, so the scores never leave registers.
+//
+// The epilogue is the binding unit (16 scores per lane against 8 MFMAs), so it is pared
+// down to the minimum:
+//   - Q arrives multiplied by log2(e) and both bias tables are scaled likewise, so that
+//     y = x*log2(e) comes out of the matrix product and SiLU(x) = ln2 * y / (1 + 2^-y);
+//     ln2 and 1/n are applied once to the output accumulators;
+//   - the positional bias is Toeplitz: the window of the (reversed, scaled) table that a key
+//     tile needs sits in LDS and initialises the score accumulators, so adding it is free;
+//   - time gaps are taken from 32-bit timestamps relative to the request's first one; for a
+//     32x32 block whose smallest and largest gap fall into the same log2 bucket (almost
+//     every block away from the diagonal) the time bias is one scalar; other blocks take
+//     the bucket per score; requests spanning >= 2^31 s (or models with more than 32
+//     buckets) use 64-bit gaps per score;
+//   - the causal select is applied only in blocks that touch the diagonal.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attention_bf16_mfma(HstuDims hd, uint32_t layer, const uint16_t* __restrict__ q,
-                                                           const float* __restrict__ pos,
-                                                           const float* __restrict__ time, KvView kv,
-                                                           const ReqDev* __restrict__ reqs,
-                                                           const uint32_t* __restrict__ tiles,
-                                                           const int32_t* __restrict__ page_tables,
-                                                           const long long* __restrict__ ts,
-                                                           uint16_t* __restrict__ o) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[64][64 + kLdsPad];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[64][64 + kLdsPad];
-  __shared__ long long s_ts[64];
-  __shared__ float s_time[64];
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+struct AttnShared {
+  uint16_t Ks[64][64 + kLdsPad];
+  uint16_t Vs[64][64 + kLdsPad];
+  long long ts64[64];
+  uint32_t tk[64];
+  float pos[192];
+  float time[64];
+};
+
+__device__ __forceinline__ uint32_t bucket_u32(uint32_t dt, uint32_t n_time) {
+  const uint32_t b = dt > 1 ? 31u - static_cast<uint32_t>(__clz(static_cast<int>(dt))) : 0u;
+  return b < n_time - 1 ? b : n_time - 1;
+}
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// y * sigmoid(y / log2 e) without the ln2 factor: y / (1 + 2^-y)
+__device__ __forceinline__ float silu_log2(float y) {
+  return y * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-y));
+}
+
+__global__ __launch_bounds__(256, 2) void attention_bf16_mfma(HstuDims hd, uint32_t layer, const uint16_t* __restrict__ q,
+                                                              const float* __restrict__ pos,
+                                                              const float* __restrict__ time, KvView kv,
+                                                              const ReqDev* __restrict__ reqs,
+                                                              const uint32_t* __restrict__ tiles,
+                                                              const int32_t* __restrict__ page_tables,
+                                                              const long long* __restrict__ ts,
+                                                              uint16_t* __restrict__ o) {
+  __shared__ __attribute__((aligned(16))) AttnShared sm;
   const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, li = lane & 31;
   const uint32_t r = tiles[2 * blockIdx.x], qt = tiles[2 * blockIdx.x + 1], h = blockIdx.y;
   const ReqDev rq = reqs[r];
@@ -288,11 +332,25 @@ __global__ __launch_bounds__(256) void attention_bf16_mfma(HstuDims hd, uint32_t
   const uint32_t qi = q0 + 32 * wave + li;      // this lane's query
   const bool q_ok = qi < T;
   const uint32_t p = P + qi;                    // its absolute position
+  const bool wave_active = q0 + 32 * wave < T;
+  const uint32_t wave_first = P + q0 + 32 * wave;
   const uint32_t wave_last = P + (q0 + 32 * wave + 31 < T - 1 ? q0 + 32 * wave + 31 : T - 1);
   const uint32_t block_last = P + (q0 + 127 < T - 1 ? q0 + 127 : T - 1);
-  if (tid < 64) s_time[tid] = tid < hd.n_time ? time[(static_cast<uint64_t>(layer) * hd.H + h) * hd.n_time + tid] : 0.0f;
+  const long long* tsr = ts + rq.ts_off;
+  const long long ts_base = tsr[0];
+  const long long span = tsr[S - 1] - ts_base;
+  const bool fast = hd.n_time <= 32 && span >= 0 && span < (1ll << 31);
+  if (tid < 64) sm.time[tid] = tid < hd.n_time ? time[(static_cast<uint64_t>(layer) * hd.H + h) * hd.n_time + tid] * kLog2e : 0.0f;
   const float* pos_h = pos + (static_cast<uint64_t>(layer) * hd.H + h) * hd.n_pos;
-  const long long ts_q = q_ok ? ts[rq.ts_off + p] : 0;
+  const long long ts_q = q_ok ? tsr[p] : ts_base;
+  const uint32_t tq = static_cast<uint32_t>(ts_q - ts_base);
+  uint32_t tq_first = 0, tq_last = 0;
+  if (wave_active) {
+    tq_first = static_cast<uint32_t>(tsr[wave_first] - ts_base);
+    tq_last = static_cast<uint32_t>(tsr[wave_last] - ts_base);
+  }
+  tq_first = __builtin_amdgcn_readfirstlane(tq_first);
+  tq_last = __builtin_amdgcn_readfirstlane(tq_last);
 
   // Q^T operand: lane (g, li) holds query li, d_h elements 16*st + 8*g .. +8
   bf16x8 qf[4];
@@ -310,6 +368,7 @@ __global__ __launch_bounds__(256) void attention_bf16_mfma(HstuDims hd, uint32_t
 
   const uint64_t koff = kv_block_offset(hd, layer, 0, h, 2), voff = kv_block_offset(hd, layer, 1, h, 2);
   const uint32_t n_tiles = block_last / 64 + 1;
+  const uint32_t pos_lane = 127 - 32 * wave - li + 4 * g;  // this lane's offset into the window
   for (uint32_t kt = 0; kt < n_tiles; ++kt) {
     const uint32_t j0 = kt * 64;
     // ---- stage the tile ----
@@ -326,7 +385,7 @@ __global__ __launch_bounds__(256) void attention_bf16_mfma(HstuDims hd, uint32_t
                                                  (static_cast<uint64_t>(j % hd.pt) * 64 + part * 8) * 2);
         else if (part == 0) atomicAdd(&kv.counters[kCtrBadPages], 1ull);
       }
-      *reinterpret_cast<uint4*>(&Ks[row][part * 8]) = kval;
+      *reinterpret_cast<uint4*>(&sm.Ks[row][part * 8]) = kval;
       // V^T: row = d_h element, part = 8 consecutive keys (inside one page: page_tokens % 8 == 0)
       uint4 vval = make_uint4(0, 0, 0, 0);
       const uint32_t jv = j0 + part * 8;
@@ -344,39 +403,64 @@ __global__ __launch_bounds__(256) void attention_bf16_mfma(HstuDims hd, uint32_t
           }
         }
       }
-      *reinterpret_cast<uint4*>(&Vs[row][part * 8]) = vval;
+      *reinterpret_cast<uint4*>(&sm.Vs[row][part * 8]) = vval;
     }
-    if (tid < 64) s_ts[tid] = (j0 + tid < S) ? ts[rq.ts_off + j0 + tid] : 0;
+    if (tid < 64) {
+      const long long t = (j0 + tid < S) ? tsr[j0 + tid] : ts_base;
+      sm.ts64[tid] = t;
+      sm.tk[tid] = static_cast<uint32_t>(t - ts_base);
+    }
+    if (tid >= 64 && tid < 64 + 191) {
+      // window of the reversed positional table: entry m holds pos[(P + q0 + 127 - j0) - m] * log2 e
+      const uint32_t m = tid - 64;
+      const int64_t i = static_cast<int64_t>(P + q0 + 127) - j0 - m;
+      sm.pos[m] = i >= 0 ? pos_h[i < static_cast<int64_t>(hd.n_pos) - 1 ? i : hd.n_pos - 1] * kLog2e : 0.0f;
+    }
     __syncthreads();
 
     // ---- two 32-key sub-blocks ----
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb) {
       const uint32_t kb = j0 + 32 * sb;
-      if (kb > wave_last) continue;  // every key of the sub-block lies after every query of this wave
+      if (!wave_active || kb > wave_last) continue;  // every key of the sub-block lies after every query of this wave
+      const float* pw = sm.pos + pos_lane + 32 * sb;
       f32x16 sacc;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) sacc[e] = 0.0f;
+      for (int e = 0; e < 16; ++e) sacc[e] = pw[8 * (e / 4) + (e % 4)];
 #pragma unroll
       for (int st = 0; st < 4; ++st) {
-        const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Ks[32 * sb + li][16 * st + 8 * g]));
+        const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&sm.Ks[32 * sb + li][16 * st + 8 * g]));
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], sacc, 0, 0, 0);
       }
-      // sacc[e]: key kb + 8*(e/4) + 4*g + e%4, query li
+      // sacc[e]: key kb + 8*(e/4) + 4*g + e%4, query li; already y = (q.k + pos) * log2 e
       uint32_t pk[8];
+      const bool diag = kb + 31 > wave_first;
+      bool uniform = false;
+      float c_time = 0.0f;
+      if (fast && !diag) {
+        const uint32_t tk_first = __builtin_amdgcn_readfirstlane(sm.tk[32 * sb]);
+        const uint32_t tk_last = __builtin_amdgcn_readfirstlane(sm.tk[32 * sb + 31]);
+        const uint32_t bmin = bucket_u32(tq_first - tk_last, hd.n_time), bmax = bucket_u32(tq_last - tk_first, hd.n_time);
+        uniform = bmin == bmax;
+        c_time = sm.time[bmin];
+      }
+      if (uniform) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const uint32_t jl = 32 * sb + 8 * (e / 4) + 4 * g + (e % 4);
-        const uint32_t j = j0 + jl;
-        float a = 0.0f;
-        if (q_ok && j <= p) {
-          const uint32_t rel = p - j < hd.n_pos - 1 ? p - j : hd.n_pos - 1;
-          const float s = sacc[e] + pos_h[rel] + s_time[time_bucket(ts_q - s_ts[jl], hd.n_time)];
-          a = silu(s);
+        for (int e = 0; e < 16; e += 2)
+          pk[e >> 1] = pack_bf16x2(silu_log2(sacc[e] + c_time), silu_log2(sacc[e + 1] + c_time));
+      } else {
+        const int lim = static_cast<int>(p) - static_cast<int>(kb) - 4 * static_cast<int>(g);  // key offset <= lim is visible
+        float a[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int off = 8 * (e / 4) + (e % 4);
+          const uint32_t jl = 32 * sb + off + 4 * g;
+          const uint32_t bkt = fast ? bucket_u32(tq - sm.tk[jl], hd.n_time) : time_bucket(ts_q - sm.ts64[jl], hd.n_time);
+          const float v = silu_log2(sacc[e] + sm.time[bkt]);
+          a[e] = off <= lim ? v : 0.0f;
         }
-        const uint32_t bits = f2bf(a);
-        if (e & 1) pk[e >> 1] |= bits << 16;
-        else pk[e >> 1] = bits;
+#pragma unroll
+        for (int e = 0; e < 16; e += 2) pk[e >> 1] = pack_bf16x2(a[e], a[e + 1]);
       }
       // P^T operand of step s2 = elements 8*s2 .. 8*s2+7: keys kb + 16*s2 + {4g..4g+3, 8+4g..8+4g+3}
 #pragma unroll
@@ -384,7 +468,7 @@ __global__ __launch_bounds__(256) void attention_bf16_mfma(HstuDims hd, uint32_t
         const bf16x8 pf = __builtin_bit_cast(bf16x8, make_uint4(pk[4 * s2], pk[4 * s2 + 1], pk[4 * s2 + 2], pk[4 * s2 + 3]));
 #pragma unroll
         for (int db = 0; db < 2; ++db) {
-          const uint16_t* vrow = &Vs[32 * db + li][32 * sb + 16 * s2 + 4 * g];
+          const uint16_t* vrow = &sm.Vs[32 * db + li][32 * sb + 16 * s2 + 4 * g];
           const uint2 lo = *reinterpret_cast<const uint2*>(vrow);
           const uint2 hi = *reinterpret_cast<const uint2*>(vrow + 8);
           const bf16x8 vf = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
@@ -394,19 +478,27 @@ __global__ __launch_bounds__(256) void attention_bf16_mfma(HstuDims hd, uint32_t
     }
     __syncthreads();
   }
-  // oacc[db][e]: d_h element 32*db + 8*(e/4) + 4*g + e%4 of query li
+  // oacc[db][e]: d_h element 32*db + 8*(e/4) + 4*g + e%4 of query li; undo the log2 e scaling, apply 1/n
   if (q_ok) {
+    const float sc = hd.inv_n * kLn2;
     uint16_t* orow = o + static_cast<uint64_t>(rq.x_off + qi) * hd.d + h * 64;
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
       for (int e4 = 0; e4 < 4; ++e4) {
         uint2 w;
-        w.x = f2bf(oacc[db][4 * e4] * hd.inv_n) | (static_cast<uint32_t>(f2bf(oacc[db][4 * e4 + 1] * hd.inv_n)) << 16);
-        w.y = f2bf(oacc[db][4 * e4 + 2] * hd.inv_n) | (static_cast<uint32_t>(f2bf(oacc[db][4 * e4 + 3] * hd.inv_n)) << 16);
+        w.x = pack_bf16x2(oacc[db][4 * e4] * sc, oacc[db][4 * e4 + 1] * sc);
+        w.y = pack_bf16x2(oacc[db][4 * e4 + 2] * sc, oacc[db][4 * e4 + 3] * sc);
         *reinterpret_cast<uint2*>(orow + 32 * db + 8 * e4 + 4 * g) = w;
       }
   }
+}
+
+// q * log2(e) for callers that hand the attention kernel an unscaled query matrix
+__global__ void scale_bf16(const uint16_t* __restrict__ in, uint16_t* __restrict__ out, uint64_t n, float s) {
+  for (uint64_t k = blockIdx.x * static_cast<uint64_t>(blockDim.x) + threadIdx.x; k < n;
+       k += static_cast<uint64_t>(gridDim.x) * blockDim.x)
+    out[k] = f2bf(bf2f(in[k]) * s);
 }
 
 template <typename T>
@@ -482,6 +574,14 @@ hipError_t launch_attention(const HstuDims& hd, uint32_t layer, const void* q, c
                        static_cast<const float*>(q), pos, time, kv, sl.reqs, sl.row_req, sl.N, page_tables,
                        reinterpret_cast<const long long*>(ts), static_cast<float*>(o));
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_scale_q(const void* in, void* out, uint64_t n, hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  const uint32_t blocks = static_cast<uint32_t>((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+  hipLaunchKernelGGL(scale_bf16, dim3(blocks), dim3(256), 0, stream, static_cast<const uint16_t*>(in),
+                     static_cast<uint16_t*>(out), n, kLog2e);
   return hipGetLastError();
 }
 

@@ -104,6 +104,8 @@ hipError_t launch_gemm_back(const HstuDims& hd, const void* g, const void* w2t, 
 hipError_t launch_attention(const HstuDims& hd, uint32_t layer, const void* q, const float* pos,
                             const float* time, const KvView& kv, const StepLists& sl,
                             const int32_t* page_tables, const int64_t* ts, void* o, hipStream_t stream);
+// q must already be multiplied by log2(e) for bf16 models (launch_gemm_front stores it that way)
+hipError_t launch_scale_q(const void* in, void* out, uint64_t n, hipStream_t stream);
 hipError_t launch_transpose_weights(const void* w, void* wt, uint32_t rows, uint32_t cols, uint32_t elem,
                                     hipStream_t stream);
 

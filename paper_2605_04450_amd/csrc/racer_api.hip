@@ -552,6 +552,22 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   return RACER_OK;
 }
 
+// Activation workspace of a step: six [rows][d] matrices (xn, u, q, o and two layer buffers).
+int32_t ensure_hstu_ws(racer_pool* p, uint64_t N, uint64_t d, uint64_t esize, hipStream_t stream) {
+  if (p->hw_rows >= N && p->hw_d == d && p->hw_esize == esize) return RACER_OK;
+  HIP_TRY(hipStreamSynchronize(stream));
+  HIP_TRY(hipStreamSynchronize(p->last_stream));
+  if (p->hw_buf) HIP_TRY(hipFree(p->hw_buf));
+  p->hw_buf = nullptr;
+  p->hw_rows = 0;
+  const uint64_t slot = (N * d * esize + 255) & ~255ull;
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->hw_buf), slot * 6));
+  p->hw_rows = N;
+  p->hw_d = d;
+  p->hw_esize = esize;
+  return RACER_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -568,18 +584,8 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
   if (N == 0) return RACER_OK;
   if (!page_tables || !x_in || !ts || !out) return RACER_EINVAL;
   const racer_hstu_cfg& c = m->cfg;
-  const uint64_t d = c.d, mat = static_cast<uint64_t>(N) * d * ctx.esize;
-  const uint64_t slot = (mat + 255) & ~255ull;
-  if (p->hw_rows < N || p->hw_d != d || p->hw_esize != ctx.esize) {  // xn, u, q, o, two layer buffers
-    HIP_TRY(hipStreamSynchronize(stream));
-    if (p->hw_buf) HIP_TRY(hipFree(p->hw_buf));
-    p->hw_buf = nullptr;
-    p->hw_rows = 0;
-    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->hw_buf), slot * 6));
-    p->hw_rows = N;
-    p->hw_d = d;
-    p->hw_esize = ctx.esize;
-  }
+  const uint64_t d = c.d;
+  if ((rc = ensure_hstu_ws(p, N, d, ctx.esize, stream))) return rc;
   const uint64_t stride = ((static_cast<uint64_t>(p->hw_rows) * d * ctx.esize) + 255) & ~255ull;
   uint8_t* xn = p->hw_buf;
   uint8_t* u = xn + stride;
@@ -588,8 +594,6 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
   uint8_t* xb[2] = {o + stride, o + 2 * stride};
   const bool bf16 = c.elem == RACER_ELEM_BF16;
   const uint64_t w1_layer = d * 4 * d * ctx.esize, w2_layer = d * d * ctx.esize;
-  const float* f = nullptr;
-  (void)f;
   const void* x_cur = x_in;
   for (uint32_t l = 0; l < c.L; ++l) {
     void* x_next = (l + 1 == c.L) ? out : static_cast<void*>(xb[l & 1]);
@@ -638,6 +642,14 @@ int32_t hstu_attn_paged(racer_pool_t* p, racer_hstu_t* m, uint32_t layer, const 
   p->last_stream = stream;
   if (ctx.sl.N == 0) return RACER_OK;
   if (!page_tables || !q || !ts || !o) return RACER_EINVAL;
+  if (m->cfg.elem == RACER_ELEM_BF16) {
+    // the MFMA kernel takes q * log2(e); hstu_step's projection writes it that way, here it is a pre-pass
+    if ((rc = ensure_hstu_ws(p, ctx.sl.N, m->cfg.d, ctx.esize, stream))) return rc;
+    const uint64_t stride = ((static_cast<uint64_t>(p->hw_rows) * m->cfg.d * ctx.esize) + 255) & ~255ull;
+    void* qs = p->hw_buf + 2 * stride;
+    HIP_TRY(racer::launch_scale_q(q, qs, static_cast<uint64_t>(ctx.sl.N) * m->cfg.d, stream));
+    q = qs;
+  }
   {
     ProfScope t(p, RACER_PROF_ATTENTION, stream);
     HIP_TRY(racer::launch_attention(ctx.hd, layer, q, static_cast<const float*>(m->w.pos),
