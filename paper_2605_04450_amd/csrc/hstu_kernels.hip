@@ -262,14 +262,17 @@ __global__ __launch_bounds__(256) void attention_f32(HstuDims hd, uint32_t layer
 }
 
 // ---------------------------------------------------------------------------------------
-// bf16 paged attention on MFMA, d_h = 64.  A block of four wavefronts owns 128 consecutive
-// queries of one request and one head; it walks the key tiles (64 keys) from position 0 to
-// its last query, staging K [key][d_h] and V^T [d_h][key] of the tile in LDS through the
-// page table.  Each wavefront computes S^T = K Q^T for its 32 queries (keys x queries, so
-// a lane ends up holding one query and 16 keys), applies bias, SiLU and the causal mask in
-// registers, and feeds the bf16 result straight back as the second operand of
-// O^T += V^T P^T: the accumulator layout of the first product is exactly the operand layout
-// of the second, so the scores never leave registers.
+// bf16 paged attention on MFMA, d_h = 64.  A block of four wavefronts owns 256 consecutive
+// queries of one request and one head (64 per wavefront, as two 32-query groups) and walks
+// a range of key tiles (64 keys), staging K [key][d_h] and V^T [d_h][key] of the tile in
+// LDS through the page table (tile k+1 is fetched into registers while tile k is used).
+// Each wavefront computes S^T = K Q^T (keys x queries, so a lane ends up holding one query
+// and 16 keys), applies bias, SiLU and the causal mask in registers, and feeds the bf16
+// result straight back as the second operand of O^T += V^T P^T: the accumulator layout of
+// the first product is the operand layout of the second, so the scores never leave
+// registers.  K rows are fed to the first product in a permuted order (bits 2 and 3 of the
+// row index swapped) so that the 8 keys a lane holds per contraction step are consecutive
+// and the matching V^T operand is one 16-byte LDS read.
 //
 // The epilogue is the binding unit (16 scores per lane against 8 MFMAs), so it is pared
 // down to the minimum:
@@ -277,25 +280,43 @@ __global__ __launch_bounds__(256) void attention_f32(HstuDims hd, uint32_t layer
 //     y = x*log2(e) comes out of the matrix product and SiLU(x) = ln2 * y / (1 + 2^-y);
 //     ln2 and 1/n are applied once to the output accumulators;
 //   - the positional bias is Toeplitz: the window of the (reversed, scaled) table that a key
-//     tile needs sits in LDS and initialises the score accumulators, so adding it is free;
+//     tile needs sits in LDS, in four copies shifted by one element each so that every lane
+//     can read its 8 consecutive entries as aligned 16-byte words, and initialises the score
+//     accumulators, so adding it costs no arithmetic;
 //   - time gaps are taken from 32-bit timestamps relative to the request's first one; for a
-//     32x32 block whose smallest and largest gap fall into the same log2 bucket (almost
-//     every block away from the diagonal) the time bias is one scalar; other blocks take
-//     the bucket per score; requests spanning >= 2^31 s (or models with more than 32
-//     buckets) use 64-bit gaps per score;
+//     32x32 block whose smallest and largest gap fall into the same log2 bucket (most blocks
+//     away from the diagonal) the time bias is one scalar; if they fall into adjacent
+//     buckets it is a compare-and-select per score; other blocks take the bucket per score;
+//     requests spanning >= 2^31 s (or models with more than 32 buckets) use 64-bit gaps;
 //   - the causal select is applied only in blocks that touch the diagonal.
 // ---------------------------------------------------------------------------------------
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr uint32_t kPosWinMax = 320;  // 256 queries + 64 keys - 1 distances per tile, padded
 
-struct AttnShared {
+struct AttnTile {  // one staged key tile
   uint16_t Ks[64][64 + kLdsPad];
   uint16_t Vs[64][64 + kLdsPad];
-  long long ts64[64];
-  uint32_t tk[64];
-  float pos[192];
-  float time[64];
+  uint32_t tk[64];             // key timestamps relative to the request's first one
+  float pos[4][kPosWinMax + 4];  // copy s holds window entry x at [s][4 + x - s]
 };
+
+struct AttnShared {
+  AttnTile tile;  // the next tile travels in registers while this one is consumed
+  float time[64];
+  int32_t pages[kAttnMaxItemPages];  // page ids of the item's key range (-1: outside the pool)
+};
+
+// page index and offset inside the page of token j (page_tokens is usually a power of two)
+__device__ __forceinline__ void split_token(const HstuDims& hd, uint32_t j, uint32_t* page_idx, uint32_t* in_page) {
+  if (hd.pt_shift < 32) {
+    *page_idx = j >> hd.pt_shift;
+    *in_page = j & (hd.pt - 1);
+  } else {
+    *page_idx = j / hd.pt;
+    *in_page = j % hd.pt;
+  }
+}
 
 __device__ __forceinline__ uint32_t bucket_u32(uint32_t dt, uint32_t n_time) {
   const uint32_t b = dt > 1 ? 31u - static_cast<uint32_t>(__clz(static_cast<int>(dt))) : 0u;
@@ -315,183 +336,371 @@ __device__ __forceinline__ float silu_log2(float y) {
   return y * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-y));
 }
 
-__global__ __launch_bounds__(256, 2) void attention_bf16_mfma(HstuDims hd, uint32_t layer, const uint16_t* __restrict__ q,
+// NQB = 32-query groups per wavefront: 1 -> 128 queries per block and four resident blocks per CU,
+// 2 -> 256 queries per block (each staged tile serves twice the queries) and two resident blocks.
+template <int NQB>
+__global__ __launch_bounds__(256, NQB == 1 ? 4 : 2) void attention_bf16_mfma(HstuDims hd, uint32_t layer, const uint16_t* __restrict__ q,
                                                               const float* __restrict__ pos,
                                                               const float* __restrict__ time, KvView kv,
                                                               const ReqDev* __restrict__ reqs,
-                                                              const uint32_t* __restrict__ tiles,
+                                                              const AttnItem* __restrict__ items,
+                                                              float* __restrict__ partials,
                                                               const int32_t* __restrict__ page_tables,
                                                               const long long* __restrict__ ts,
                                                               uint16_t* __restrict__ o) {
+  constexpr uint32_t kQ = 128 * NQB;     // queries per block
+  constexpr uint32_t kPosWin = kQ + 64;  // distances a tile can need (kQ + 63), padded
   __shared__ __attribute__((aligned(16))) AttnShared sm;
   const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, li = lane & 31;
-  const uint32_t r = tiles[2 * blockIdx.x], qt = tiles[2 * blockIdx.x + 1], h = blockIdx.y;
+  const AttnItem item = items[blockIdx.x / hd.H];
+  const uint32_t r = item.req, qt = item.qt, h = blockIdx.x % hd.H;
   const ReqDev rq = reqs[r];
   const uint32_t P = rq.prefix_len, T = rq.new_len, S = P + T;
-  const uint32_t q0 = qt * 128;                 // first query (index among the new tokens) of the block
-  const uint32_t qi = q0 + 32 * wave + li;      // this lane's query
-  const bool q_ok = qi < T;
-  const uint32_t p = P + qi;                    // its absolute position
-  const bool wave_active = q0 + 32 * wave < T;
-  const uint32_t wave_first = P + q0 + 32 * wave;
-  const uint32_t wave_last = P + (q0 + 32 * wave + 31 < T - 1 ? q0 + 32 * wave + 31 : T - 1);
-  const uint32_t block_last = P + (q0 + 127 < T - 1 ? q0 + 127 : T - 1);
+  const uint32_t q0 = qt * kQ;  // first query (index among the new tokens) of the block
   const long long* tsr = ts + rq.ts_off;
   const long long ts_base = tsr[0];
   const long long span = tsr[S - 1] - ts_base;
   const bool fast = hd.n_time <= 32 && span >= 0 && span < (1ll << 31);
-  if (tid < 64) sm.time[tid] = tid < hd.n_time ? time[(static_cast<uint64_t>(layer) * hd.H + h) * hd.n_time + tid] * kLog2e : 0.0f;
+  if (tid < 64) sm.time[tid] = tid < hd.n_time ? time[(static_cast<uint64_t>(layer) * hd.H + h) * hd.n_time + tid] : 0.0f;
   const float* pos_h = pos + (static_cast<uint64_t>(layer) * hd.H + h) * hd.n_pos;
-  const long long ts_q = q_ok ? tsr[p] : ts_base;
-  const uint32_t tq = static_cast<uint32_t>(ts_q - ts_base);
-  uint32_t tq_first = 0, tq_last = 0;
-  if (wave_active) {
-    tq_first = static_cast<uint32_t>(tsr[wave_first] - ts_base);
-    tq_last = static_cast<uint32_t>(tsr[wave_last] - ts_base);
-  }
-  tq_first = __builtin_amdgcn_readfirstlane(tq_first);
-  tq_last = __builtin_amdgcn_readfirstlane(tq_last);
 
-  // Q^T operand: lane (g, li) holds query li, d_h elements 16*st + 8*g .. +8
-  bf16x8 qf[4];
+  // per 32-query group qb of this wavefront
+  uint32_t ql[NQB], p[NQB], grp_first[NQB], grp_last[NQB], tq[NQB], tq_first[NQB], tq_last[NQB];
+  bool q_ok[NQB], grp_active[NQB];
+  long long ts_q[NQB];
+  bf16x8 qf[NQB][4];  // Q^T operand: lane (g, li) holds query li, d_h elements 16*st + 8*g .. +8
+  f32x16 oacc[NQB][2];
 #pragma unroll
-  for (int st = 0; st < 4; ++st) {
-    uint4 val = make_uint4(0, 0, 0, 0);
-    if (q_ok) val = *reinterpret_cast<const uint4*>(q + static_cast<uint64_t>(rq.x_off + qi) * hd.d + h * 64 + 16 * st + 8 * g);
-    qf[st] = __builtin_bit_cast(bf16x8, val);
+  for (int qb = 0; qb < NQB; ++qb) {
+    ql[qb] = 32 * NQB * wave + 32 * qb + li;  // query index inside the block
+    const uint32_t qi = q0 + ql[qb];
+    q_ok[qb] = qi < T;
+    p[qb] = P + qi;
+    const uint32_t first = q0 + 32 * NQB * wave + 32 * qb;
+    grp_active[qb] = first < T;
+    grp_first[qb] = P + first;
+    grp_last[qb] = P + (first + 31 < T - 1 ? first + 31 : T - 1);
+    ts_q[qb] = q_ok[qb] ? tsr[p[qb]] : ts_base;
+    tq[qb] = static_cast<uint32_t>(ts_q[qb] - ts_base);
+    uint32_t a = 0, b = 0;
+    if (grp_active[qb]) {
+      a = static_cast<uint32_t>(tsr[grp_first[qb]] - ts_base);
+      b = static_cast<uint32_t>(tsr[grp_last[qb]] - ts_base);
+    }
+    tq_first[qb] = __builtin_amdgcn_readfirstlane(a);
+    tq_last[qb] = __builtin_amdgcn_readfirstlane(b);
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+      uint4 val = make_uint4(0, 0, 0, 0);
+      if (q_ok[qb]) val = *reinterpret_cast<const uint4*>(q + static_cast<uint64_t>(rq.x_off + qi) * hd.d + h * 64 + 16 * st + 8 * g);
+      qf[qb][st] = __builtin_bit_cast(bf16x8, val);
+    }
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[qb][b2][e] = 0.0f;
   }
-  f32x16 oacc[2];
-#pragma unroll
-  for (int b = 0; b < 2; ++b)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) oacc[b][e] = 0.0f;
 
   const uint64_t koff = kv_block_offset(hd, layer, 0, h, 2), voff = kv_block_offset(hd, layer, 1, h, 2);
-  const uint32_t n_tiles = block_last / 64 + 1;
-  const uint32_t pos_lane = 127 - 32 * wave - li + 4 * g;  // this lane's offset into the window
-  for (uint32_t kt = 0; kt < n_tiles; ++kt) {
-    const uint32_t j0 = kt * 64;
-    // ---- stage the tile ----
-#pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const uint32_t c = tid + 256 * it, row = c >> 3, part = c & 7;
-      // K: row = key, part = 8 d_h elements
-      uint4 kval = make_uint4(0, 0, 0, 0);
-      const uint32_t j = j0 + row;
-      if (j < S) {
-        const int32_t page = page_tables[rq.page_table_off + j / hd.pt];
-        if (page >= 0 && static_cast<uint32_t>(page) < kv.n_pages)
-          kval = *reinterpret_cast<const uint4*>(kv.base + static_cast<uint64_t>(page) * kv.page_size + koff +
-                                                 (static_cast<uint64_t>(j % hd.pt) * 64 + part * 8) * 2);
-        else if (part == 0) atomicAdd(&kv.counters[kCtrBadPages], 1ull);
+  const uint32_t kt_begin = item.kt_begin, kt_end = item.kt_end;
+  // the item's slice of the page table goes to LDS once, so that a tile fetch is a single
+  // global round trip instead of two dependent ones
+  uint32_t page0, unused_ip;
+  split_token(hd, kt_begin * 64, &page0, &unused_ip);
+  {
+    const uint32_t last_key = (kt_end * 64 < S ? kt_end * 64 : S) - 1;
+    uint32_t page_last;
+    split_token(hd, last_key, &page_last, &unused_ip);
+    for (uint32_t i = tid; i <= page_last - page0 && i < kAttnMaxItemPages; i += 256) {
+      int32_t pg = page_tables[rq.page_table_off + page0 + i];
+      if (pg < 0 || static_cast<uint32_t>(pg) >= kv.n_pages) {
+        atomicAdd(&kv.counters[kCtrBadPages], 1ull);
+        pg = -1;
       }
-      *reinterpret_cast<uint4*>(&sm.Ks[row][part * 8]) = kval;
-      // V^T: row = d_h element, part = 8 consecutive keys (inside one page: page_tokens % 8 == 0)
-      uint4 vval = make_uint4(0, 0, 0, 0);
-      const uint32_t jv = j0 + part * 8;
-      if (jv < S) {
-        const int32_t page = page_tables[rq.page_table_off + jv / hd.pt];
-        if (page >= 0 && static_cast<uint32_t>(page) < kv.n_pages) {
-          vval = *reinterpret_cast<const uint4*>(kv.base + static_cast<uint64_t>(page) * kv.page_size + voff +
-                                                 (static_cast<uint64_t>(row) * hd.pt + jv % hd.pt) * 2);
-          if (jv + 8 > S) {  // keys past the end of the sequence hold whatever the page held before
-            uint32_t w[4] = {vval.x, vval.y, vval.z, vval.w};
+      sm.pages[i] = pg;
+    }
+  }
+  __syncthreads();
+  const uint32_t krow = (li & 0x13) | ((li & 8) >> 1) | ((li & 4) << 1);  // K row this lane feeds as MFMA row li
+
+  // registers that carry the next tile from global memory to LDS
+  uint4 kreg[2], vreg[2];
+  uint32_t treg = 0;
+  float preg[2] = {0.0f, 0.0f};
+  // thread-constant byte offsets of its two K and two V^T chunks inside a tile that lies in one page
+  const bool one_page_tiles = hd.pt_shift < 32 && hd.pt >= 64;
+  uint32_t kconst[2], vconst[2];
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-              if (jv + e >= S) w[e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
-            vval = make_uint4(w[0], w[1], w[2], w[3]);
+  for (int it = 0; it < 2; ++it) {
+    const uint32_t c = tid + 256 * it, row = c >> 3, part = c & 7;
+    kconst[it] = row * 128 + part * 16;
+    vconst[it] = (row * hd.pt + part * 8) * 2;
+  }
+  const int32_t pos_top = static_cast<int32_t>(P + q0 + kQ - 1);  // window entry m of tile j0 is pos[pos_top - j0 - m]
+  auto fetch = [&](uint32_t kt) {
+    const uint32_t j0 = kt * 64;
+    bool done = false;
+    if (one_page_tiles && j0 + 64 <= S) {
+      // the whole tile sits in one page and inside the sequence: one scalar base, no per-thread arithmetic
+      const int32_t page = __builtin_amdgcn_readfirstlane(sm.pages[(j0 >> hd.pt_shift) - page0]);
+      if (page >= 0) {
+        const uint32_t tb = j0 & (hd.pt - 1);
+        const uint8_t* pb = kv.base + static_cast<uint64_t>(page) * kv.page_size;
+        const uint8_t* kbase = pb + koff + static_cast<uint64_t>(tb) * 128;
+        const uint8_t* vbase = pb + voff + static_cast<uint64_t>(tb) * 2;
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+          kreg[it] = *reinterpret_cast<const uint4*>(kbase + kconst[it]);
+          vreg[it] = *reinterpret_cast<const uint4*>(vbase + vconst[it]);
+        }
+        done = true;
+      }
+    }
+    if (!done) {
+#pragma unroll
+      for (int it = 0; it < 2; ++it) {
+        const uint32_t c = tid + 256 * it, row = c >> 3, part = c & 7;
+        // K: row = key, part = 8 d_h elements
+        kreg[it] = make_uint4(0, 0, 0, 0);
+        const uint32_t j = j0 + row;
+        if (j < S) {
+          uint32_t pi, ip;
+          split_token(hd, j, &pi, &ip);
+          const int32_t page = sm.pages[pi - page0];
+          if (page >= 0)
+            kreg[it] = *reinterpret_cast<const uint4*>(kv.base + static_cast<uint64_t>(page) * kv.page_size + koff +
+                                                       (static_cast<uint64_t>(ip) * 64 + part * 8) * 2);
+        }
+        // V^T: row = d_h element, part = 8 consecutive keys (inside one page: page_tokens % 8 == 0)
+        vreg[it] = make_uint4(0, 0, 0, 0);
+        const uint32_t jv = j0 + part * 8;
+        if (jv < S) {
+          uint32_t pi, ip;
+          split_token(hd, jv, &pi, &ip);
+          const int32_t page = sm.pages[pi - page0];
+          if (page >= 0) {
+            uint4 vval = *reinterpret_cast<const uint4*>(kv.base + static_cast<uint64_t>(page) * kv.page_size + voff +
+                                                         (static_cast<uint64_t>(row) * hd.pt + ip) * 2);
+            if (jv + 8 > S) {  // keys past the end of the sequence hold whatever the page held before
+              uint32_t w[4] = {vval.x, vval.y, vval.z, vval.w};
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                if (jv + e >= S) w[e >> 1] &= (e & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+              vval = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+            vreg[it] = vval;
           }
         }
       }
-      *reinterpret_cast<uint4*>(&sm.Vs[row][part * 8]) = vval;
     }
-    if (tid < 64) {
-      const long long t = (j0 + tid < S) ? tsr[j0 + tid] : ts_base;
-      sm.ts64[tid] = t;
-      sm.tk[tid] = static_cast<uint32_t>(t - ts_base);
+    // window of the reversed positional table (already scaled by log2 e); entries with a negative
+    // distance belong to keys after the query, which the causal select removes
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const uint32_t m = tid + 256 * it;
+      if (m < kPosWin) {
+        int32_t i = pos_top - static_cast<int32_t>(j0) - static_cast<int32_t>(m);
+        i = i < 0 ? 0 : (i > static_cast<int32_t>(hd.n_pos) - 1 ? static_cast<int32_t>(hd.n_pos) - 1 : i);
+        preg[it] = pos_h[i];
+      }
     }
-    if (tid >= 64 && tid < 64 + 191) {
-      // window of the reversed positional table: entry m holds pos[(P + q0 + 127 - j0) - m] * log2 e
-      const uint32_t m = tid - 64;
-      const int64_t i = static_cast<int64_t>(P + q0 + 127) - j0 - m;
-      sm.pos[m] = i >= 0 ? pos_h[i < static_cast<int64_t>(hd.n_pos) - 1 ? i : hd.n_pos - 1] * kLog2e : 0.0f;
+    if (tid < 64) treg = (j0 + tid < S) ? static_cast<uint32_t>(tsr[j0 + tid] - ts_base) : 0u;
+  };
+  auto commit = [&](AttnTile& t) {
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const uint32_t c = tid + 256 * it, row = c >> 3, part = c & 7;
+      *reinterpret_cast<uint4*>(&t.Ks[row][part * 8]) = kreg[it];
+      *reinterpret_cast<uint4*>(&t.Vs[row][part * 8]) = vreg[it];
+      if (c < kPosWin) {
+#pragma unroll
+        for (uint32_t s = 0; s < 4; ++s) t.pos[s][4 + c - s] = preg[it];  // copy s = window shifted by s
+      }
     }
-    __syncthreads();
+    if (tid < 64) t.tk[tid] = treg;
+  };
 
-    // ---- two 32-key sub-blocks ----
+  fetch(kt_begin);
+  for (uint32_t kt = kt_begin; kt < kt_end; ++kt) {
+    const uint32_t j0 = kt * 64;
+    AttnTile& tl = sm.tile;
+    if (kt != kt_begin) __syncthreads();  // every wave has finished tile kt-1
+    commit(tl);
+    __syncthreads();  // tile kt is visible
+    if (kt + 1 < kt_end) fetch(kt + 1);  // its global loads fly while this tile is consumed
+
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb) {
       const uint32_t kb = j0 + 32 * sb;
-      if (!wave_active || kb > wave_last) continue;  // every key of the sub-block lies after every query of this wave
-      const float* pw = sm.pos + pos_lane + 32 * sb;
-      f32x16 sacc;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) sacc[e] = pw[8 * (e / 4) + (e % 4)];
-#pragma unroll
-      for (int st = 0; st < 4; ++st) {
-        const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&sm.Ks[32 * sb + li][16 * st + 8 * g]));
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], sacc, 0, 0, 0);
-      }
-      // sacc[e]: key kb + 8*(e/4) + 4*g + e%4, query li; already y = (q.k + pos) * log2 e
-      uint32_t pk[8];
-      const bool diag = kb + 31 > wave_first;
-      bool uniform = false;
-      float c_time = 0.0f;
-      if (fast && !diag) {
-        const uint32_t tk_first = __builtin_amdgcn_readfirstlane(sm.tk[32 * sb]);
-        const uint32_t tk_last = __builtin_amdgcn_readfirstlane(sm.tk[32 * sb + 31]);
-        const uint32_t bmin = bucket_u32(tq_first - tk_last, hd.n_time), bmax = bucket_u32(tq_last - tk_first, hd.n_time);
-        uniform = bmin == bmax;
-        c_time = sm.time[bmin];
-      }
-      if (uniform) {
-#pragma unroll
-        for (int e = 0; e < 16; e += 2)
-          pk[e >> 1] = pack_bf16x2(silu_log2(sacc[e] + c_time), silu_log2(sacc[e + 1] + c_time));
-      } else {
-        const int lim = static_cast<int>(p) - static_cast<int>(kb) - 4 * static_cast<int>(g);  // key offset <= lim is visible
-        float a[16];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int off = 8 * (e / 4) + (e % 4);
-          const uint32_t jl = 32 * sb + off + 4 * g;
-          const uint32_t bkt = fast ? bucket_u32(tq - sm.tk[jl], hd.n_time) : time_bucket(ts_q - sm.ts64[jl], hd.n_time);
-          const float v = silu_log2(sacc[e] + sm.time[bkt]);
-          a[e] = off <= lim ? v : 0.0f;
+      if (!grp_active[0] || kb > grp_last[NQB - 1]) continue;  // nothing of this sub-block is visible to the wave
+      // operands are read from LDS right where they are consumed: holding all of them across
+      // the epilogue would push the kernel past 256 registers
+      auto k_frag = [&](int st) {
+        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&tl.Ks[32 * sb + krow][16 * st + 8 * g]));
+      };
+      auto v_frag = [&](int s2, int db) {
+        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&tl.Vs[32 * db + li][32 * sb + 16 * s2 + 8 * g]));
+      };
+      // S^T = K Q^T on top of the positional bias: lane's window entries m0 .. m0+7 and m0+16 .. m0+23
+      auto scores_begin = [&](int qb) {
+        const uint32_t m0 = (kQ - 1) - ql[qb] + 32 * sb + 8 * g;
+        const float* pw = &tl.pos[m0 & 3][4 + (m0 & ~3u)];
+        const float4 w0 = *reinterpret_cast<const float4*>(pw), w1 = *reinterpret_cast<const float4*>(pw + 4);
+        const float4 w2 = *reinterpret_cast<const float4*>(pw + 16), w3 = *reinterpret_cast<const float4*>(pw + 20);
+        f32x16 sacc;
+        sacc[0] = w0.x; sacc[1] = w0.y; sacc[2] = w0.z; sacc[3] = w0.w;
+        sacc[4] = w1.x; sacc[5] = w1.y; sacc[6] = w1.z; sacc[7] = w1.w;
+        sacc[8] = w2.x; sacc[9] = w2.y; sacc[10] = w2.z; sacc[11] = w2.w;
+        sacc[12] = w3.x; sacc[13] = w3.y; sacc[14] = w3.z; sacc[15] = w3.w;
+        return sacc;
+      };
+      // bias, SiLU, mask -> bf16 pairs.  sacc[e]: key kb + 16*(e/8) + 8*g + e%8, query li of group qb;
+      // y = (q.k + pos) * log2 e
+      auto epilogue = [&](int qb, const f32x16& sacc, uint32_t pk[8]) {
+        const bool diag = kb + 31 > grp_first[qb];
+        int mode = 2;  // 0: one time bias for the block, 1: two adjacent buckets, 2: bucket per score (+ mask)
+        float c_lo = 0.0f, c_hi = 0.0f;
+        uint32_t thr = 0;
+        if (fast && !diag) {
+          const uint32_t tk_first = __builtin_amdgcn_readfirstlane(tl.tk[32 * sb]);
+          const uint32_t tk_last = __builtin_amdgcn_readfirstlane(tl.tk[32 * sb + 31]);
+          const uint32_t bmin = bucket_u32(tq_first[qb] - tk_last, hd.n_time);
+          const uint32_t bmax = bucket_u32(tq_last[qb] - tk_first, hd.n_time);
+          c_lo = sm.time[bmin];
+          if (bmin == bmax) {
+            mode = 0;
+          } else if (bmax == bmin + 1) {
+            mode = 1;
+            c_hi = sm.time[bmax];
+            thr = 2u << bmin;  // gaps >= 2^(bmin+1) belong to the upper bucket
+          }
         }
+        if (mode == 0) {
 #pragma unroll
-        for (int e = 0; e < 16; e += 2) pk[e >> 1] = pack_bf16x2(a[e], a[e + 1]);
-      }
-      // P^T operand of step s2 = elements 8*s2 .. 8*s2+7: keys kb + 16*s2 + {4g..4g+3, 8+4g..8+4g+3}
+          for (int e = 0; e < 16; e += 2)
+            pk[e >> 1] = pack_bf16x2(silu_log2(sacc[e] + c_lo), silu_log2(sacc[e + 1] + c_lo));
+        } else if (mode == 1) {
+          const uint32_t* tkp = &tl.tk[32 * sb + 8 * g];
+          float a[16];
 #pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        const bf16x8 pf = __builtin_bit_cast(bf16x8, make_uint4(pk[4 * s2], pk[4 * s2 + 1], pk[4 * s2 + 2], pk[4 * s2 + 3]));
+          for (int e = 0; e < 16; ++e) {
+            const uint32_t gap = tq[qb] - tkp[16 * (e / 8) + (e % 8)];
+            a[e] = silu_log2(sacc[e] + (gap >= thr ? c_hi : c_lo));
+          }
 #pragma unroll
-        for (int db = 0; db < 2; ++db) {
-          const uint16_t* vrow = &sm.Vs[32 * db + li][32 * sb + 16 * s2 + 4 * g];
-          const uint2 lo = *reinterpret_cast<const uint2*>(vrow);
-          const uint2 hi = *reinterpret_cast<const uint2*>(vrow + 8);
-          const bf16x8 vf = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[db], 0, 0, 0);
+          for (int e = 0; e < 16; e += 2) pk[e >> 1] = pack_bf16x2(a[e], a[e + 1]);
+        } else {
+          const int lim = static_cast<int>(p[qb]) - static_cast<int>(kb) - 8 * static_cast<int>(g);  // visible: key offset <= lim
+          float a[16];
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int off = 16 * (e / 8) + (e % 8);
+            const uint32_t jl = 32 * sb + off + 8 * g;
+            const uint32_t bkt = fast ? bucket_u32(tq[qb] - tl.tk[jl], hd.n_time)
+                                      : time_bucket(ts_q[qb] - (j0 + jl < S ? tsr[j0 + jl] : ts_base), hd.n_time);
+            const float v = silu_log2(sacc[e] + sm.time[bkt]);
+            a[e] = off <= lim ? v : 0.0f;
+          }
+#pragma unroll
+          for (int e = 0; e < 16; e += 2) pk[e >> 1] = pack_bf16x2(a[e], a[e + 1]);
+        }
+      };
+      // O^T += V^T P^T; the P^T operand of step s2 = elements 8*s2 .. 8*s2+7: keys kb + 16*s2 + 8*g + 0..7
+      auto accumulate = [&](int qb, const uint32_t pk[8]) {
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8 pf = __builtin_bit_cast(bf16x8, make_uint4(pk[4 * s2], pk[4 * s2 + 1], pk[4 * s2 + 2], pk[4 * s2 + 3]));
+#pragma unroll
+          for (int db = 0; db < 2; ++db)
+            oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag(s2, db), pf, oacc[qb][db], 0, 0, 0);
+        }
+      };
+      if (NQB == 2 && grp_active[NQB - 1] && kb <= grp_last[0]) {
+        // both query groups see the sub-block: their two product chains are issued interleaved,
+        // and each group's second product runs while the other group's epilogue executes
+        f32x16 s0 = scores_begin(0), s1 = scores_begin(NQB - 1);
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+          const bf16x8 kf = k_frag(st);
+          s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][st], s0, 0, 0, 0);
+          s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[NQB - 1][st], s1, 0, 0, 0);
+        }
+        uint32_t pk0[8], pk1[8];
+        epilogue(0, s0, pk0);
+        accumulate(0, pk0);
+        epilogue(NQB - 1, s1, pk1);
+        accumulate(NQB - 1, pk1);
+      } else {
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) {
+          if (!grp_active[qb] || kb > grp_last[qb]) continue;
+          f32x16 s0 = scores_begin(qb);
+#pragma unroll
+          for (int st = 0; st < 4; ++st) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(st), qf[qb][st], s0, 0, 0, 0);
+          uint32_t pk0[8];
+          epilogue(qb, s0, pk0);
+          accumulate(qb, pk0);
         }
       }
     }
-    __syncthreads();
   }
-  // oacc[db][e]: d_h element 32*db + 8*(e/4) + 4*g + e%4 of query li; undo the log2 e scaling, apply 1/n
-  if (q_ok) {
-    const float sc = hd.inv_n * kLn2;
-    uint16_t* orow = o + static_cast<uint64_t>(rq.x_off + qi) * hd.d + h * 64;
+  // oacc[qb][db][e]: d_h element 32*db + 8*(e/4) + 4*g + e%4 of the lane's query; undo the log2 e scaling, apply 1/n
+  const float sc = hd.inv_n * kLn2;
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
+  for (int qb = 0; qb < NQB; ++qb) {
+    if (item.slot != kDirect) {
+      // part of a split query tile: fp32 partial [slot][head][query][d_h], summed by attention_reduce
+      float* prow = partials + ((static_cast<uint64_t>(item.slot) * hd.H + h) * kQ + ql[qb]) * 64;
 #pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4) {
-        uint2 w;
-        w.x = pack_bf16x2(oacc[db][4 * e4] * sc, oacc[db][4 * e4 + 1] * sc);
-        w.y = pack_bf16x2(oacc[db][4 * e4 + 2] * sc, oacc[db][4 * e4 + 3] * sc);
-        *reinterpret_cast<uint2*>(orow + 32 * db + 8 * e4 + 4 * g) = w;
-      }
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4)
+          *reinterpret_cast<float4*>(prow + 32 * db + 8 * e4 + 4 * g) =
+              make_float4(oacc[qb][db][4 * e4] * sc, oacc[qb][db][4 * e4 + 1] * sc, oacc[qb][db][4 * e4 + 2] * sc,
+                          oacc[qb][db][4 * e4 + 3] * sc);
+    } else if (q_ok[qb]) {
+      uint16_t* orow = o + static_cast<uint64_t>(rq.x_off + q0 + ql[qb]) * hd.d + h * 64;
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          uint2 w;
+          w.x = pack_bf16x2(oacc[qb][db][4 * e4] * sc, oacc[qb][db][4 * e4 + 1] * sc);
+          w.y = pack_bf16x2(oacc[qb][db][4 * e4 + 2] * sc, oacc[qb][db][4 * e4 + 3] * sc);
+          *reinterpret_cast<uint2*>(orow + 32 * db + 8 * e4 + 4 * g) = w;
+        }
+    }
   }
+}
+
+// Sum the fp32 partials of a split query tile in chunk order and write the bf16 output.
+__global__ __launch_bounds__(256) void attention_reduce(HstuDims hd, uint32_t q_block, const ReqDev* __restrict__ reqs,
+                                                        const AttnGroup* __restrict__ groups,
+                                                        const float* __restrict__ partials, uint16_t* __restrict__ o) {
+  const AttnGroup gr = groups[blockIdx.x / hd.H];
+  const uint32_t h = blockIdx.x % hd.H;
+  const ReqDev rq = reqs[gr.req];
+  for (uint32_t idx = threadIdx.x; idx < q_block * 16; idx += 256) {
+    const uint32_t row = idx >> 4, c4 = idx & 15;
+    const uint32_t qi = gr.qt * q_block + row;
+    if (qi >= rq.new_len) continue;
+    float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (uint32_t k = 0; k < gr.chunks; ++k) {
+      const float4 v = *reinterpret_cast<const float4*>(
+          partials + ((static_cast<uint64_t>(gr.slot0 + k) * hd.H + h) * q_block + row) * 64 + 4 * c4);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    uint2 w;
+    w.x = pack_bf16x2(acc.x, acc.y);
+    w.y = pack_bf16x2(acc.z, acc.w);
+    *reinterpret_cast<uint2*>(o + static_cast<uint64_t>(rq.x_off + qi) * hd.d + h * 64 + 4 * c4) = w;
+  }
+}
+
+__global__ void scale_f32(const float* __restrict__ in, float* __restrict__ out, uint64_t n, float s) {
+  for (uint64_t k = blockIdx.x * static_cast<uint64_t>(blockDim.x) + threadIdx.x; k < n;
+       k += static_cast<uint64_t>(gridDim.x) * blockDim.x)
+    out[k] = in[k] * s;
 }
 
 // q * log2(e) for callers that hand the attention kernel an unscaled query matrix
@@ -565,15 +774,30 @@ hipError_t launch_attention(const HstuDims& hd, uint32_t layer, const void* q, c
                             void* o, hipStream_t stream) {
   if (sl.N == 0) return hipSuccess;
   if (hd.elem == 1) {
-    hipLaunchKernelGGL(attention_bf16_mfma, dim3(sl.n_tiles, hd.H), dim3(256), 0, stream, hd, layer,
-                       static_cast<const uint16_t*>(q), pos, time, kv, sl.reqs, sl.tiles, page_tables,
-                       reinterpret_cast<const long long*>(ts), static_cast<uint16_t*>(o));
+    if (sl.q_block == 128)
+      hipLaunchKernelGGL(attention_bf16_mfma<1>, dim3(sl.n_items * hd.H), dim3(256), 0, stream, hd, layer,
+                         static_cast<const uint16_t*>(q), pos, time, kv, sl.reqs, sl.items, sl.partials, page_tables,
+                         reinterpret_cast<const long long*>(ts), static_cast<uint16_t*>(o));
+    else
+      hipLaunchKernelGGL(attention_bf16_mfma<2>, dim3(sl.n_items * hd.H), dim3(256), 0, stream, hd, layer,
+                         static_cast<const uint16_t*>(q), pos, time, kv, sl.reqs, sl.items, sl.partials, page_tables,
+                         reinterpret_cast<const long long*>(ts), static_cast<uint16_t*>(o));
+    if (sl.n_groups)
+      hipLaunchKernelGGL(attention_reduce, dim3(sl.n_groups * hd.H), dim3(256), 0, stream, hd, sl.q_block, sl.reqs,
+                         sl.groups, sl.partials, static_cast<uint16_t*>(o));
   } else {
     const uint32_t items = sl.N * hd.H;
     hipLaunchKernelGGL(attention_f32, dim3((items + 3) / 4), dim3(256), 0, stream, hd, layer,
                        static_cast<const float*>(q), pos, time, kv, sl.reqs, sl.row_req, sl.N, page_tables,
                        reinterpret_cast<const long long*>(ts), static_cast<float*>(o));
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_scale_bias(const float* in, float* out, uint64_t n, hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  const uint32_t blocks = static_cast<uint32_t>((n + 255) / 256 < 8192 ? (n + 255) / 256 : 8192);
+  hipLaunchKernelGGL(scale_f32, dim3(blocks), dim3(256), 0, stream, in, out, n, kLog2e);
   return hipGetLastError();
 }
 

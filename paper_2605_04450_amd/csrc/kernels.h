@@ -70,6 +70,7 @@ hipError_t launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t 
 struct HstuDims {
   uint32_t L, d, H, dh, elem, pt, n_pos, n_time;
   float inv_n, eps;
+  uint32_t pt_shift;  // log2(pt) when pt is a power of two, else 32
 };
 
 struct ReqDev {  // device copy of one request
@@ -84,12 +85,30 @@ struct KvView {
   unsigned long long* counters;
 };
 
-// row -> request map and work list built on the host for one step
+constexpr uint32_t kAttnQueries = 256;
+constexpr uint32_t kAttnMaxItemPages = 1024;  // page-table entries one attention item may span  // queries per attention work item (bf16 path)
+
+// One attention work item: q_block (128 or 256) queries of one request against the key tiles [kt_begin, kt_end)
+// (64 keys each).  A query tile whose key range was cut into several items accumulates
+// through fp32 partial slots (slot .. slot + chunks - 1) that a reduction pass adds up in
+// order; an item that covers its whole key range writes the output directly (slot = kDirect).
+struct AttnItem {
+  uint32_t req, qt, kt_begin, kt_end, slot, pad;
+};
+struct AttnGroup {
+  uint32_t req, qt, slot0, chunks;
+};
+constexpr uint32_t kDirect = 0xFFFFFFFFu;
+
+// row -> request map and work lists built on the host for one step
 struct StepLists {
   const ReqDev* reqs;        // [B]
   const uint32_t* row_req;   // [N] request of each new-token row
-  const uint32_t* tiles;     // attention work items, longest first: (req << 16 | q_tile) pairs as 2 words
-  uint32_t n_tiles;
+  const AttnItem* items;     // largest first
+  const AttnGroup* groups;   // query tiles that were split
+  float* partials;           // [slot][head][q_block][64]
+  uint32_t n_items, n_groups;
+  uint32_t q_block;          // queries per item: 128 or 256
   uint32_t B, N;
 };
 
@@ -104,7 +123,9 @@ hipError_t launch_gemm_back(const HstuDims& hd, const void* g, const void* w2t, 
 hipError_t launch_attention(const HstuDims& hd, uint32_t layer, const void* q, const float* pos,
                             const float* time, const KvView& kv, const StepLists& sl,
                             const int32_t* page_tables, const int64_t* ts, void* o, hipStream_t stream);
-// q must already be multiplied by log2(e) for bf16 models (launch_gemm_front stores it that way)
+// bf16 models: pos and time must be the tables multiplied by log2(e) (launch_scale_bias), and
+// q must already be multiplied by log2(e) (launch_gemm_front stores it that way)
+hipError_t launch_scale_bias(const float* in, float* out, uint64_t n, hipStream_t stream);
 hipError_t launch_scale_q(const void* in, void* out, uint64_t n, hipStream_t stream);
 hipError_t launch_transpose_weights(const void* w, void* wt, uint32_t rows, uint32_t cols, uint32_t elem,
                                     hipStream_t stream);

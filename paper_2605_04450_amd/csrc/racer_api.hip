@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -113,6 +114,8 @@ struct racer_pool {
   uint8_t* hw_buf = nullptr;
   uint64_t hl_cap = 0;
   uint8_t* hl_dev = nullptr;
+  uint64_t hp_cap = 0;  // fp32 partial outputs of split attention items
+  uint8_t* hp_dev = nullptr;
   Staging hstage;
   // optional per-kernel-class timing with events on the caller's stream
   struct ProfMark { hipEvent_t a, b; int kind; };
@@ -149,6 +152,8 @@ struct racer_hstu {
   racer_hstu_weights w;
   void* w1t = nullptr;  // bf16 models: [L][4d][d], the MFMA kernels want output-major weights
   void* w2t = nullptr;  // [L][d][d]
+  float* pos_s = nullptr;   // bf16 models: pos and time tables times log2(e), as the attention kernel wants them
+  float* time_s = nullptr;
 };
 
 namespace {
@@ -294,6 +299,7 @@ int32_t pool_destroy(racer_pool_t* p) {
     (void)hipFree(p->d_counters);
     (void)hipFree(p->hw_buf);
     (void)hipFree(p->hl_dev);
+    (void)hipFree(p->hp_dev);
   }
   delete p;
   return RACER_OK;
@@ -448,10 +454,16 @@ int32_t hstu_model_create(const racer_hstu_cfg* cfg, const racer_hstu_weights* w
         e = racer::launch_transpose_weights(static_cast<const uint16_t*>(w->w2) + l * d * d,
                                             static_cast<uint16_t*>(m->w2t) + l * d * d, cfg->d, cfg->d, 1, nullptr);
     }
+    const uint64_t n_pos_all = static_cast<uint64_t>(cfg->L) * cfg->H * cfg->n_pos;
+    const uint64_t n_time_all = static_cast<uint64_t>(cfg->L) * cfg->H * cfg->n_time;
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&m->pos_s), n_pos_all * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&m->time_s), n_time_all * sizeof(float));
+    if (e == hipSuccess) e = racer::launch_scale_bias(static_cast<const float*>(w->pos), m->pos_s, n_pos_all, nullptr);
+    if (e == hipSuccess) e = racer::launch_scale_bias(static_cast<const float*>(w->time), m->time_s, n_time_all, nullptr);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
       hstu_model_destroy(m);
-      return hip_fail(e, "hstu_model_create weight transpose");
+      return hip_fail(e, "hstu_model_create weight preparation");
     }
   }
   *out = m;
@@ -462,6 +474,8 @@ int32_t hstu_model_destroy(racer_hstu_t* m) {
   if (!m) return RACER_EINVAL;
   (void)hipFree(m->w1t);
   (void)hipFree(m->w2t);
+  (void)hipFree(m->pos_s);
+  (void)hipFree(m->time_s);
   delete m;
   return RACER_OK;
 }
@@ -497,22 +511,63 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   }
   if (N >= (1ull << 31) || B >= (1u << 24)) return RACER_EINVAL;
 
-  struct Tile { uint32_t req, qt; uint64_t work; };
-  std::vector<Tile> tiles;
+  // Attention work items.  The score matrix of a request is a staircase: late query tiles see
+  // many more key tiles than early ones, and one long request would otherwise set the
+  // kernel's duration.  Key ranges are therefore cut into chunks of at most `chunk` tiles,
+  // sized so that about two items per resident block slot exist, and launched largest first.
+  uint32_t q_block = 128;
+  if (const char* ev = std::getenv("RACER_EXP_QBLOCK")) q_block = static_cast<uint32_t>(std::atoi(ev)) == 256 ? 256 : 128;
+  struct QTile { uint32_t req, qt, n_kt; };
+  std::vector<QTile> qtiles;
+  uint64_t visits = 0;
   for (uint32_t r = 0; r < B; ++r) {
     const uint32_t T = reqs[r].new_len;
-    for (uint32_t qt = 0; qt * 128 < T; ++qt) {
-      const uint64_t last = static_cast<uint64_t>(reqs[r].prefix_len) + std::min<uint64_t>(qt * 128 + 127, T - 1);
-      tiles.push_back({r, qt, last / 64 + 1});
+    for (uint32_t qt = 0; qt * q_block < T; ++qt) {
+      const uint64_t last = static_cast<uint64_t>(reqs[r].prefix_len) + std::min<uint64_t>(qt * q_block + q_block - 1, T - 1);
+      qtiles.push_back({r, qt, static_cast<uint32_t>(last / 64 + 1)});
+      visits += last / 64 + 1;
     }
   }
-  std::stable_sort(tiles.begin(), tiles.end(), [](const Tile& a, const Tile& b) { return a.work > b.work; });
+  const uint64_t block_slots = q_block == 128 ? 1024 : 512;  // 256 CUs x resident blocks
+  uint32_t chunk = static_cast<uint32_t>(std::max<uint64_t>(8, (visits * c.H + 2 * block_slots - 1) / (2 * block_slots)));
+  if (const char* ev = std::getenv("RACER_EXP_CHUNK")) chunk = static_cast<uint32_t>(std::atoi(ev));
+  // an item's slice of the page table must fit the kernel's LDS copy
+  const uint32_t chunk_cap = static_cast<uint32_t>((static_cast<uint64_t>(racer::kAttnMaxItemPages) - 2) * c.page_tokens / 64);
+  chunk = std::min(chunk, std::max<uint32_t>(1, chunk_cap));
+  std::vector<racer::AttnItem> items;
+  std::vector<racer::AttnGroup> groups;
+  uint32_t n_slots = 0;
+  for (const QTile& t : qtiles) {
+    const uint32_t chunks = (t.n_kt + chunk - 1) / chunk;
+    const uint32_t per = (t.n_kt + chunks - 1) / chunks;
+    if (chunks > 1) groups.push_back({t.req, t.qt, n_slots, chunks});
+    for (uint32_t k = 0; k < chunks; ++k) {
+      const uint32_t b = k * per, e = std::min(t.n_kt, b + per);
+      items.push_back({t.req, t.qt, b, e, chunks > 1 ? n_slots + k : racer::kDirect, 0});
+    }
+    if (chunks > 1) n_slots += chunks;
+  }
+  std::stable_sort(items.begin(), items.end(), [](const racer::AttnItem& a, const racer::AttnItem& b) {
+    return a.kt_end - a.kt_begin > b.kt_end - b.kt_begin;
+  });
+  const uint64_t partial_bytes = static_cast<uint64_t>(n_slots) * c.H * q_block * 64 * sizeof(float);
+  if (partial_bytes > p->hp_cap) {
+    HIP_TRY(hipStreamSynchronize(p->last_stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    if (p->hp_dev) HIP_TRY(hipFree(p->hp_dev));
+    p->hp_dev = nullptr;
+    p->hp_cap = 0;
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->hp_dev), partial_bytes + partial_bytes / 4));
+    p->hp_cap = partial_bytes + partial_bytes / 4;
+  }
 
   const uint64_t bytes_reqs = sizeof(racer::ReqDev) * std::max<uint32_t>(B, 1);
   const uint64_t bytes_rows = sizeof(uint32_t) * std::max<uint64_t>(N, 1);
-  const uint64_t bytes_tiles = sizeof(uint32_t) * 2 * std::max<size_t>(tiles.size(), 1);
-  const uint64_t off_rows = (bytes_reqs + 255) & ~255ull, off_tiles = (off_rows + bytes_rows + 255) & ~255ull;
-  const uint64_t total = off_tiles + bytes_tiles;
+  const uint64_t bytes_items = sizeof(racer::AttnItem) * std::max<size_t>(items.size(), 1);
+  const uint64_t bytes_groups = sizeof(racer::AttnGroup) * std::max<size_t>(groups.size(), 1);
+  const uint64_t off_rows = (bytes_reqs + 255) & ~255ull, off_items = (off_rows + bytes_rows + 255) & ~255ull;
+  const uint64_t off_groups = (off_items + bytes_items + 255) & ~255ull;
+  const uint64_t total = off_groups + bytes_groups;
   if (total > p->hl_cap) {
     HIP_TRY(hipStreamSynchronize(p->last_stream));
     if (p->hl_dev) HIP_TRY(hipFree(p->hl_dev));
@@ -527,26 +582,30 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   if (rc) return rc;
   racer::ReqDev* hr = reinterpret_cast<racer::ReqDev*>(hbuf);
   uint32_t* hrow = reinterpret_cast<uint32_t*>(hbuf + off_rows);
-  uint32_t* ht = reinterpret_cast<uint32_t*>(hbuf + off_tiles);
   for (uint32_t r = 0; r < B; ++r) {
     hr[r] = racer::ReqDev{reqs[r].prefix_len, reqs[r].new_len, static_cast<uint32_t>(reqs[r].page_table_off),
                           static_cast<uint32_t>(reqs[r].ts_off), static_cast<uint32_t>(reqs[r].x_off), 0};
     for (uint32_t i = 0; i < reqs[r].new_len; ++i) hrow[reqs[r].x_off + i] = r;
   }
-  for (size_t k = 0; k < tiles.size(); ++k) {
-    ht[2 * k] = tiles[k].req;
-    ht[2 * k + 1] = tiles[k].qt;
-  }
+  if (!items.empty()) std::memcpy(hbuf + off_items, items.data(), sizeof(racer::AttnItem) * items.size());
+  if (!groups.empty()) std::memcpy(hbuf + off_groups, groups.data(), sizeof(racer::AttnGroup) * groups.size());
   HIP_TRY(hipMemcpyAsync(p->hl_dev, hbuf, total, hipMemcpyHostToDevice, stream));
   if ((rc = p->hstage.mark(which, stream))) return rc;
 
   ctx->esize = esize;
-  ctx->hd = racer::HstuDims{c.L, c.d, c.H, c.d / c.H, c.elem, c.page_tokens, c.n_pos, c.n_time, 1.0f / c.n_scale, c.eps};
+  uint32_t pt_shift = 32;
+  for (uint32_t b = 0; b < 32; ++b)
+    if ((1u << b) == c.page_tokens) pt_shift = b;
+  ctx->hd = racer::HstuDims{c.L, c.d, c.H, c.d / c.H, c.elem, c.page_tokens, c.n_pos, c.n_time, 1.0f / c.n_scale, c.eps, pt_shift};
   ctx->kv = racer::KvView{p->base, p->page_size, static_cast<uint32_t>(p->host.n_pages()), p->d_counters};
   ctx->sl.reqs = reinterpret_cast<const racer::ReqDev*>(p->hl_dev);
   ctx->sl.row_req = reinterpret_cast<const uint32_t*>(p->hl_dev + off_rows);
-  ctx->sl.tiles = reinterpret_cast<const uint32_t*>(p->hl_dev + off_tiles);
-  ctx->sl.n_tiles = static_cast<uint32_t>(tiles.size());
+  ctx->sl.items = reinterpret_cast<const racer::AttnItem*>(p->hl_dev + off_items);
+  ctx->sl.groups = reinterpret_cast<const racer::AttnGroup*>(p->hl_dev + off_groups);
+  ctx->sl.partials = reinterpret_cast<float*>(p->hp_dev);
+  ctx->sl.n_items = static_cast<uint32_t>(items.size());
+  ctx->sl.n_groups = static_cast<uint32_t>(groups.size());
+  ctx->sl.q_block = q_block;
   ctx->sl.B = B;
   ctx->sl.N = static_cast<uint32_t>(N);
   return RACER_OK;
@@ -615,8 +674,9 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
     }
     {
       ProfScope t(p, RACER_PROF_ATTENTION, stream);
-      HIP_TRY(racer::launch_attention(ctx.hd, l, q, static_cast<const float*>(m->w.pos),
-                                      static_cast<const float*>(m->w.time), ctx.kv, ctx.sl, page_tables, ts, o, stream));
+      HIP_TRY(racer::launch_attention(ctx.hd, l, q, bf16 ? m->pos_s : static_cast<const float*>(m->w.pos),
+                                      bf16 ? m->time_s : static_cast<const float*>(m->w.time), ctx.kv, ctx.sl,
+                                      page_tables, ts, o, stream));
     }
     {
       ProfScope t(p, RACER_PROF_LAYERNORM, stream);
@@ -652,8 +712,10 @@ int32_t hstu_attn_paged(racer_pool_t* p, racer_hstu_t* m, uint32_t layer, const 
   }
   {
     ProfScope t(p, RACER_PROF_ATTENTION, stream);
-    HIP_TRY(racer::launch_attention(ctx.hd, layer, q, static_cast<const float*>(m->w.pos),
-                                    static_cast<const float*>(m->w.time), ctx.kv, ctx.sl, page_tables, ts, o, stream));
+    const bool bf16 = m->cfg.elem == RACER_ELEM_BF16;
+    HIP_TRY(racer::launch_attention(ctx.hd, layer, q, bf16 ? m->pos_s : static_cast<const float*>(m->w.pos),
+                                    bf16 ? m->time_s : static_cast<const float*>(m->w.time), ctx.kv, ctx.sl,
+                                    page_tables, ts, o, stream));
   }
   return RACER_OK;
 }

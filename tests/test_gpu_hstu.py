@@ -121,6 +121,24 @@ def test_bf16_prefill_ragged_lengths(L, d, H, pt, lens):
     c.close()
 
 
+def test_bf16_long_sequences_use_split_key_ranges():
+    # long enough that query tiles are cut into several key-range items whose fp32 partial
+    # outputs are summed by the reduction pass; second step scores a short tail on a long prefix
+    c = Case(8, 1, 128, 2, 64, True, 4096, 32, 4096.0, 256)
+    reqs, pts, ts, x = c.inputs([0, 0, 0], [2500, 900, 3000 + 300])
+    first = [(0, 2500, reqs[0][2], reqs[0][3], 0), (0, 900, reqs[1][2], reqs[1][3], 2500),
+             (0, 3000, reqs[2][2], reqs[2][3], 3400)]
+    xa = np.concatenate([x[:2500], x[2500:3400], x[3400:6400]])
+    ga, oa = c.run_gpu(first, pts, ts, xa), c.run_oracle(first, pts, ts, xa)
+    assert_close(ga, oa, True, "long prefill")
+    second = [(3000, 300, reqs[2][2], reqs[2][3], 0)]
+    xb = x[6400:6700]
+    gb, ob = c.run_gpu(second, pts, ts, xb), c.run_oracle(second, pts, ts, xb)
+    assert_close(gb, ob, True, "short tail on a long cached prefix")
+    assert c.pool.stats()["bad_pages"] == 0
+    c.close()
+
+
 @pytest.mark.parametrize("bf16", [False, True])
 def test_prefix_reuse_two_steps(bf16):
     # step 1 prefills, step 2 scores new tokens against the cached prefix (KV reuse)
