@@ -51,40 +51,92 @@ __device__ __forceinline__ uint64_t kv_block_offset(const HstuDims& hd, uint32_t
   return ((static_cast<uint64_t>(layer) * 2 + kv) * hd.H + head) * hd.pt * hd.dh * esize;
 }
 
+// page index and offset inside the page of token j (page_tokens is usually a power of two)
+__device__ __forceinline__ void split_token(const HstuDims& hd, uint32_t j, uint32_t* page_idx, uint32_t* in_page) {
+  if (hd.pt_shift < 32) {
+    *page_idx = j >> hd.pt_shift;
+    *in_page = j & (hd.pt - 1);
+  } else {
+    *page_idx = j / hd.pt;
+    *in_page = j % hd.pt;
+  }
+}
+
 // ---------------------------------------------------------------------------------------
-// LayerNorm over d (optionally times a gate row), one wavefront per row, two-pass in fp32
+// LayerNorm over d (optionally times a gate row), one wavefront per row, two-pass in fp32.
+// A lane owns chunks of 8 consecutive elements (16-byte accesses for bf16), d <= 1024.
 // ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void load8(const float* p, float v[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16_t* p, float v[8]) {
+  const uint4 a = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    v[2 * k] = __uint_as_float(w[k] << 16);
+    v[2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
+  }
+}
+__device__ __forceinline__ void store8(float* p, const float v[8]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ void store8(bf16_t* p, const float v[8]) {
+  uint4 a;
+  a.x = f2bf(v[0]) | (static_cast<uint32_t>(f2bf(v[1])) << 16);
+  a.y = f2bf(v[2]) | (static_cast<uint32_t>(f2bf(v[3])) << 16);
+  a.z = f2bf(v[4]) | (static_cast<uint32_t>(f2bf(v[5])) << 16);
+  a.w = f2bf(v[6]) | (static_cast<uint32_t>(f2bf(v[7])) << 16);
+  *reinterpret_cast<uint4*>(p) = a;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void layernorm_rows(const T* __restrict__ x, const float* __restrict__ g,
                                                       const float* __restrict__ b, const T* __restrict__ gate,
                                                       T* __restrict__ y, uint32_t N, uint32_t d, float eps) {
   const uint32_t lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= N) return;
-  float v[16];
+  const uint32_t chunks = d / 8;
+  float v[2][8];
   float s = 0.0f;
 #pragma unroll
-  for (int k = 0; k < 16; ++k) {
+  for (int k = 0; k < 2; ++k) {
     const uint32_t c = lane + 64 * k;
-    v[k] = c < d ? load_elem(x, static_cast<uint64_t>(row) * d + c) : 0.0f;
-    s += v[k];
+    if (c < chunks) load8(x + static_cast<uint64_t>(row) * d + 8 * c, v[k]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (c >= chunks) v[k][e] = 0.0f;
+      s += v[k][e];
+    }
   }
   const float mean = wave_sum(s) / d;
   float q = 0.0f;
 #pragma unroll
-  for (int k = 0; k < 16; ++k) {
-    const uint32_t c = lane + 64 * k;
-    const float dv = c < d ? v[k] - mean : 0.0f;
-    q += dv * dv;
-  }
+  for (int k = 0; k < 2; ++k)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float dv = (lane + 64 * k < chunks) ? v[k][e] - mean : 0.0f;
+      q += dv * dv;
+    }
   const float rstd = 1.0f / sqrtf(wave_sum(q) / d + eps);
 #pragma unroll
-  for (int k = 0; k < 16; ++k) {
+  for (int k = 0; k < 2; ++k) {
     const uint32_t c = lane + 64 * k;
-    if (c < d) {
-      float o = (v[k] - mean) * rstd * g[c] + b[c];
-      if (gate) o *= load_elem(gate, static_cast<uint64_t>(row) * d + c);
-      store_elem(y, static_cast<uint64_t>(row) * d + c, o);
+    if (c >= chunks) continue;
+    float gg[8], bb[8], o[8];
+    load8(g + 8 * c, gg);
+    load8(b + 8 * c, bb);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (v[k][e] - mean) * rstd * gg[e] + bb[e];
+    if (gate) {
+      float gt[8];
+      load8(gate + static_cast<uint64_t>(row) * d + 8 * c, gt);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] *= gt[e];
     }
+    store8(y + static_cast<uint64_t>(row) * d + 8 * c, o);
   }
 }
 
@@ -193,6 +245,131 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma(const uint16_t* __restrict
       const uint32_t row = m0 + 32 * wave + 8 * (r / 4) + 4 * g + (r % 4);
       if (row < M) epi(row, n0 + 32 * cb + li, acc[cb][r]);
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// Pointwise projection of bf16 models: [U|V|Q|K] = SiLU(Xn W1 + b1) on MFMA, one block per
+// (row tile, 64 output columns).  Row tiles never cross a request (host-built list), and 64
+// columns are exactly one head's slice of U, V, Q or K, so a block has one destination:
+// the results go through LDS and leave as 16-byte stores - rows of U/Q, token rows of the K
+// block, and key-contiguous runs of the transposed V block.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gemm_front_bf16(HstuDims hd, uint32_t layer, const uint16_t* __restrict__ A,
+                                                       const uint16_t* __restrict__ Bt, const float* __restrict__ b1,
+                                                       uint16_t* __restrict__ u, uint16_t* __restrict__ q, KvView kv,
+                                                       const ReqDev* __restrict__ reqs,
+                                                       const RowTile* __restrict__ row_tiles,
+                                                       const int32_t* __restrict__ page_tables) {
+  __shared__ __attribute__((aligned(16))) uint16_t As[128][64 + kLdsPad];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[64][64 + kLdsPad];
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, li = lane & 31;
+  const RowTile rt = row_tiles[blockIdx.x];
+  const uint32_t m0 = rt.row0, rows = rt.rows, n0 = blockIdx.y * 64, K = hd.d;
+  f32x16 acc[2];
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[cb][r] = 0.0f;
+  for (uint32_t k0 = 0; k0 < K; k0 += 64) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const uint32_t c = tid + 256 * it, row = c >> 3, part = c & 7;
+      uint4 val = make_uint4(0, 0, 0, 0);
+      if (row < rows) val = *reinterpret_cast<const uint4*>(A + static_cast<uint64_t>(m0 + row) * K + k0 + part * 8);
+      *reinterpret_cast<uint4*>(&As[row][part * 8]) = val;
+    }
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const uint32_t c = tid + 256 * it, row = c >> 3, part = c & 7;
+      *reinterpret_cast<uint4*>(&Bs[row][part * 8]) =
+          *reinterpret_cast<const uint4*>(Bt + static_cast<uint64_t>(n0 + row) * K + k0 + part * 8);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&As[32 * wave + li][16 * st + 8 * g]));
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) {
+        const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Bs[32 * cb + li][16 * st + 8 * g]));
+        acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[cb], 0, 0, 0);
+      }
+    }
+    __syncthreads();
+  }
+  // ---- epilogue: bias + SiLU (+ log2 e for Q) -> bf16 tile in LDS (reusing As) ----
+  const uint32_t which = n0 / hd.d, head = (n0 % hd.d) / 64;  // 0 U, 1 V, 2 Q, 3 K
+  const float qscale = which == 2 ? 1.4426950408889634f : 1.0f;
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb) {
+    const float bias = b1[n0 + 32 * cb + li];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const uint32_t row = 32 * wave + 8 * (r / 4) + 4 * g + (r % 4);
+      As[row][32 * cb + li] = f2bf(silu(acc[cb][r] + bias) * qscale);
+    }
+  }
+  __syncthreads();
+  if (which == 0 || which == 2) {
+    uint16_t* dst = which == 0 ? u : q;
+    for (uint32_t idx = tid; idx < 128 * 8; idx += 256) {
+      const uint32_t row = idx >> 3, part = idx & 7;
+      if (row < rows)
+        *reinterpret_cast<uint4*>(dst + static_cast<uint64_t>(m0 + row) * hd.d + head * 64 + part * 8) =
+            *reinterpret_cast<const uint4*>(&As[row][part * 8]);
+    }
+    return;
+  }
+  const ReqDev rq = reqs[rt.req];
+  const uint32_t pos0 = rq.prefix_len + (m0 - rq.x_off);  // sequence position of the tile's first row
+  if (which == 3) {  // K block: [token][d_h], one 128-byte row per token
+    const uint64_t koff = kv_block_offset(hd, layer, 0, head, 2);
+    for (uint32_t idx = tid; idx < 128 * 8; idx += 256) {
+      const uint32_t row = idx >> 3, part = idx & 7;
+      if (row >= rows) continue;
+      uint32_t pi, ip;
+      split_token(hd, pos0 + row, &pi, &ip);
+      const int32_t page = page_tables[rq.page_table_off + pi];
+      if (page < 0 || static_cast<uint32_t>(page) >= kv.n_pages) {
+        if (part == 0) atomicAdd(&kv.counters[kCtrBadPages], 1ull);
+        continue;
+      }
+      *reinterpret_cast<uint4*>(kv.base + static_cast<uint64_t>(page) * kv.page_size + koff + (static_cast<uint64_t>(ip) * 64 + part * 8) * 2) =
+          *reinterpret_cast<const uint4*>(&As[row][part * 8]);
+    }
+    return;
+  }
+  // V block, stored transposed [d_h][token]: a thread takes one d_h row and 8 consecutive tokens
+  const uint64_t voff = kv_block_offset(hd, layer, 1, head, 2);
+  for (uint32_t idx = tid; idx < 64 * 16; idx += 256) {
+    const uint32_t dh = idx >> 4, t0 = (idx & 15) * 8;
+    if (t0 >= rows) continue;
+    uint32_t pi, ip;
+    split_token(hd, pos0 + t0, &pi, &ip);
+    const bool whole = t0 + 8 <= rows && (ip & 7) == 0;  // the 8 tokens are one aligned run inside a page
+    if (whole) {
+      const int32_t page = page_tables[rq.page_table_off + pi];
+      if (page < 0 || static_cast<uint32_t>(page) >= kv.n_pages) {
+        if (dh == 0) atomicAdd(&kv.counters[kCtrBadPages], 1ull);
+        continue;
+      }
+      uint32_t w[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) w[e] = As[t0 + 2 * e][dh] | (static_cast<uint32_t>(As[t0 + 2 * e + 1][dh]) << 16);
+      *reinterpret_cast<uint4*>(kv.base + static_cast<uint64_t>(page) * kv.page_size + voff + (static_cast<uint64_t>(dh) * hd.pt + ip) * 2) =
+          make_uint4(w[0], w[1], w[2], w[3]);
+    } else {
+      for (uint32_t e = 0; e < 8 && t0 + e < rows; ++e) {
+        split_token(hd, pos0 + t0 + e, &pi, &ip);
+        const int32_t page = page_tables[rq.page_table_off + pi];
+        if (page < 0 || static_cast<uint32_t>(page) >= kv.n_pages) {
+          if (dh == 0) atomicAdd(&kv.counters[kCtrBadPages], 1ull);
+          continue;
+        }
+        *reinterpret_cast<uint16_t*>(kv.base + static_cast<uint64_t>(page) * kv.page_size + voff + (static_cast<uint64_t>(dh) * hd.pt + ip) * 2) =
+            As[t0 + e][dh];
+      }
+    }
+  }
 }
 
 // fp32 GEMM for the small configuration: one thread per output, W is [K][Nout]
@@ -306,17 +483,6 @@ struct AttnShared {
   float time[64];
   int32_t pages[kAttnMaxItemPages];  // page ids of the item's key range (-1: outside the pool)
 };
-
-// page index and offset inside the page of token j (page_tokens is usually a power of two)
-__device__ __forceinline__ void split_token(const HstuDims& hd, uint32_t j, uint32_t* page_idx, uint32_t* in_page) {
-  if (hd.pt_shift < 32) {
-    *page_idx = j >> hd.pt_shift;
-    *in_page = j & (hd.pt - 1);
-  } else {
-    *page_idx = j / hd.pt;
-    *in_page = j % hd.pt;
-  }
-}
 
 __device__ __forceinline__ uint32_t bucket_u32(uint32_t dt, uint32_t n_time) {
   const uint32_t b = dt > 1 ? 31u - static_cast<uint32_t>(__clz(static_cast<int>(dt))) : 0u;
@@ -741,9 +907,9 @@ hipError_t launch_gemm_front(const HstuDims& hd, uint32_t layer, const void* xn,
                              hipStream_t stream) {
   if (sl.N == 0) return hipSuccess;
   if (hd.elem == 1) {
-    FrontEpilogue<bf16_t> epi{hd, layer, b1, static_cast<bf16_t*>(u), static_cast<bf16_t*>(q), kv, sl.reqs, sl.row_req, page_tables};
-    hipLaunchKernelGGL(gemm_bf16_mfma<FrontEpilogue<bf16_t>>, dim3((sl.N + 127) / 128, 4 * hd.d / 64), dim3(256), 0,
-                       stream, static_cast<const uint16_t*>(xn), static_cast<const uint16_t*>(w1), sl.N, hd.d, epi);
+    hipLaunchKernelGGL(gemm_front_bf16, dim3(sl.n_row_tiles, 4 * hd.d / 64), dim3(256), 0, stream, hd, layer,
+                       static_cast<const uint16_t*>(xn), static_cast<const uint16_t*>(w1), b1, static_cast<uint16_t*>(u),
+                       static_cast<uint16_t*>(q), kv, sl.reqs, sl.row_tiles, page_tables);
   } else {
     FrontEpilogue<float> epi{hd, layer, b1, static_cast<float*>(u), static_cast<float*>(q), kv, sl.reqs, sl.row_req, page_tables};
     const uint64_t total = static_cast<uint64_t>(sl.N) * 4 * hd.d;

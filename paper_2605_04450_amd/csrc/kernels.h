@@ -100,12 +100,19 @@ struct AttnGroup {
 };
 constexpr uint32_t kDirect = 0xFFFFFFFFu;
 
+// Up to 128 consecutive new-token rows of one request (projection GEMM tile)
+struct RowTile {
+  uint32_t row0, rows, req, pad;
+};
+
 // row -> request map and work lists built on the host for one step
 struct StepLists {
   const ReqDev* reqs;        // [B]
   const uint32_t* row_req;   // [N] request of each new-token row
   const AttnItem* items;     // largest first
   const AttnGroup* groups;   // query tiles that were split
+  const RowTile* row_tiles;  // projection tiles, none crosses a request
+  uint32_t n_row_tiles;
   float* partials;           // [slot][head][q_block][64]
   uint32_t n_items, n_groups;
   uint32_t q_block;          // queries per item: 128 or 256

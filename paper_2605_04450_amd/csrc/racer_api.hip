@@ -565,9 +565,15 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   const uint64_t bytes_rows = sizeof(uint32_t) * std::max<uint64_t>(N, 1);
   const uint64_t bytes_items = sizeof(racer::AttnItem) * std::max<size_t>(items.size(), 1);
   const uint64_t bytes_groups = sizeof(racer::AttnGroup) * std::max<size_t>(groups.size(), 1);
+  std::vector<racer::RowTile> row_tiles;
+  for (uint32_t r = 0; r < B; ++r)
+    for (uint32_t t0 = 0; t0 < reqs[r].new_len; t0 += 128)
+      row_tiles.push_back({static_cast<uint32_t>(reqs[r].x_off) + t0, std::min<uint32_t>(128, reqs[r].new_len - t0), r, 0});
+  const uint64_t bytes_row_tiles = sizeof(racer::RowTile) * std::max<size_t>(row_tiles.size(), 1);
   const uint64_t off_rows = (bytes_reqs + 255) & ~255ull, off_items = (off_rows + bytes_rows + 255) & ~255ull;
   const uint64_t off_groups = (off_items + bytes_items + 255) & ~255ull;
-  const uint64_t total = off_groups + bytes_groups;
+  const uint64_t off_row_tiles = (off_groups + bytes_groups + 255) & ~255ull;
+  const uint64_t total = off_row_tiles + bytes_row_tiles;
   if (total > p->hl_cap) {
     HIP_TRY(hipStreamSynchronize(p->last_stream));
     if (p->hl_dev) HIP_TRY(hipFree(p->hl_dev));
@@ -589,6 +595,7 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   }
   if (!items.empty()) std::memcpy(hbuf + off_items, items.data(), sizeof(racer::AttnItem) * items.size());
   if (!groups.empty()) std::memcpy(hbuf + off_groups, groups.data(), sizeof(racer::AttnGroup) * groups.size());
+  if (!row_tiles.empty()) std::memcpy(hbuf + off_row_tiles, row_tiles.data(), sizeof(racer::RowTile) * row_tiles.size());
   HIP_TRY(hipMemcpyAsync(p->hl_dev, hbuf, total, hipMemcpyHostToDevice, stream));
   if ((rc = p->hstage.mark(which, stream))) return rc;
 
@@ -606,6 +613,8 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   ctx->sl.n_items = static_cast<uint32_t>(items.size());
   ctx->sl.n_groups = static_cast<uint32_t>(groups.size());
   ctx->sl.q_block = q_block;
+  ctx->sl.row_tiles = reinterpret_cast<const racer::RowTile*>(p->hl_dev + off_row_tiles);
+  ctx->sl.n_row_tiles = static_cast<uint32_t>(row_tiles.size());
   ctx->sl.B = B;
   ctx->sl.N = static_cast<uint32_t>(N);
   return RACER_OK;
