@@ -257,6 +257,97 @@ __global__ __launch_bounds__(256) void emb_probe_gather(EmbView v, MissWs ws, co
 }
 
 // ---------------------------------------------------------------------------------------
+// Probe + hit gather, fast path for 32-way sets, one lookup per output row and rows that are
+// a multiple of 128 bytes.  Eight lanes serve one lookup: they read the set's 128-byte tag
+// line as eight 16-byte words, agree on the way with three cross-lane steps, and copy the
+// row with 16-byte lanes, so a wavefront keeps eight independent lookups in flight per
+// instruction and nothing is serialised over the lookups of a batch.
+// ---------------------------------------------------------------------------------------
+template <int PASSES>  // row_bytes / 128
+__global__ __launch_bounds__(256) void emb_probe_gather_w32(EmbView v, MissWs ws, const int64_t* __restrict__ ids,
+                                                            uint32_t n, uint8_t* __restrict__ out,
+                                                            uint8_t* __restrict__ hit_flags, uint32_t batch) {
+  constexpr uint32_t kPerBlock = 256;  // lookups per block: 4 waves x 8 groups x 8 rounds
+  __shared__ uint32_t s_miss[kPerBlock];
+  __shared__ uint32_t s_n, s_base_m, s_base_d;
+  __shared__ uint32_t s_cnt[3];
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, grp = lane >> 3, j = lane & 7;
+  if (tid == 0) s_n = 0;
+  if (tid < 3) s_cnt[tid] = 0;
+  if (blockIdx.x == 0 && tid < 3) ws.ctr_next[tid] = 0;  // the next call's list counters
+  __syncthreads();
+  const uint4* tags4 = reinterpret_cast<const uint4*>(v.tags);
+  uint32_t n_hit = 0, n_valid = 0, n_invalid = 0;  // counted by lane 0 of each group
+#pragma unroll 2
+  for (uint32_t round = 0; round < 8; ++round) {
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * kPerBlock + (round * 4 + wave) * 8 + grp;
+    const bool active = i < n;
+    const int64_t id = active ? ids[i] : -1;
+    const bool valid = active && id >= 0 && static_cast<uint64_t>(id) < v.rows;
+    const uint32_t id32 = static_cast<uint32_t>(id);
+    const uint32_t set = valid ? set_of(v, id) : 0;
+    const uint32_t nw = valid ? ways_of(v, set) : 0;
+    uint32_t cand = 255;  // lowest matching way seen by this lane
+    if (4 * j < nw) {
+      const uint4 t = tags4[static_cast<uint64_t>(set) * 8 + j];
+      if (4 * j + 3 < nw && t.w == id32) cand = 4 * j + 3;
+      if (4 * j + 2 < nw && t.z == id32) cand = 4 * j + 2;
+      if (4 * j + 1 < nw && t.y == id32) cand = 4 * j + 1;
+      if (t.x == id32) cand = 4 * j;
+    }
+#pragma unroll
+    for (int o = 4; o > 0; o >>= 1) {
+      const uint32_t other = __shfl_xor(cand, o, kWave);
+      cand = other < cand ? other : cand;
+    }
+    const bool hit = valid && cand != 255;
+    const bool miss = valid && !hit;
+    if (j == 0) {
+      n_hit += hit;
+      n_valid += valid;
+      n_invalid += active && !valid;
+      if (hit_flags && active) hit_flags[i] = hit ? 1 : 0;
+    }
+    uint8_t* dst = out + i * v.row_bytes;
+    if (hit) {
+      if (j == 0) v.stamps[static_cast<uint64_t>(set) * 32 + cand] = batch;
+      const uint8_t* src = v.base + slot_offset(v, set, cand);
+      uint4 r[PASSES];
+#pragma unroll
+      for (int c = 0; c < PASSES; ++c) r[c] = *reinterpret_cast<const uint4*>(src + 16 * (j + 8 * c));
+#pragma unroll
+      for (int c = 0; c < PASSES; ++c) *reinterpret_cast<uint4*>(dst + 16 * (j + 8 * c)) = r[c];
+    } else if (active && !valid) {
+#pragma unroll
+      for (int c = 0; c < PASSES; ++c) *reinterpret_cast<uint4*>(dst + 16 * (j + 8 * c)) = make_uint4(0, 0, 0, 0);
+    } else if (miss && j == 0) {
+      ws.loc[i] = -2;  // replaced by the staging row once the miss is resolved
+      s_miss[atomicAdd(&s_n, 1u)] = static_cast<uint32_t>(i);
+    }
+  }
+  if (j == 0) {
+    if (n_hit) atomicAdd(&s_cnt[0], n_hit);
+    if (n_valid) atomicAdd(&s_cnt[1], n_valid);
+    if (n_invalid) atomicAdd(&s_cnt[2], n_invalid);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    // with one lookup per row the missing lookups are also the output rows that wait
+    s_base_m = s_n ? atomicAdd(&ws.ctr[0], s_n) : 0;
+    s_base_d = s_n ? atomicAdd(&ws.ctr[1], s_n) : 0;
+    if (s_cnt[1]) atomicAdd(&v.counters[kCtrLookups], static_cast<unsigned long long>(s_cnt[1]));
+    if (s_cnt[0]) atomicAdd(&v.counters[kCtrHits], static_cast<unsigned long long>(s_cnt[0]));
+    if (s_cnt[1] - s_cnt[0]) atomicAdd(&v.counters[kCtrMisses], static_cast<unsigned long long>(s_cnt[1] - s_cnt[0]));
+    if (s_cnt[2]) atomicAdd(&v.counters[kCtrInvalid], static_cast<unsigned long long>(s_cnt[2]));
+  }
+  __syncthreads();
+  for (uint32_t k = tid; k < s_n; k += 256) {
+    ws.miss_list[s_base_m + k] = s_miss[k];
+    ws.def_list[s_base_d + k] = s_miss[k];
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // Miss path.  All kernels read the list lengths from device memory and return at once
 // when the batch had no miss.
 // ---------------------------------------------------------------------------------------
@@ -524,6 +615,17 @@ hipError_t launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t 
 hipError_t launch_emb_probe(const EmbView& v, const MissWs& ws, const int64_t* ids, uint32_t n, uint32_t bag,
                             uint8_t* out, uint8_t* hit_flags, uint32_t batch, hipStream_t stream) {
   if (n == 0) return hipSuccess;
+  if (bag == 1 && v.w_max == 32 && v.row_bytes % 128 == 0 && v.row_bytes <= 1024) {
+    const dim3 grid((n + 255) / 256), block(256);
+    switch (v.row_bytes / 128) {
+#define RACER_W32_CASE(P) \
+  case P: hipLaunchKernelGGL(emb_probe_gather_w32<P>, grid, block, 0, stream, v, ws, ids, n, out, hit_flags, batch); break;
+      RACER_W32_CASE(1) RACER_W32_CASE(2) RACER_W32_CASE(3) RACER_W32_CASE(4)
+      RACER_W32_CASE(5) RACER_W32_CASE(6) RACER_W32_CASE(7) RACER_W32_CASE(8)
+#undef RACER_W32_CASE
+    }
+    return hipGetLastError();
+  }
   const uint32_t lb = (64 / bag) * bag;
   const uint32_t per_block = 4 * lb;
   const uint32_t blocks = (n + per_block - 1) / per_block;
