@@ -246,10 +246,10 @@ __global__ __launch_bounds__(256) void emb_probe_gather(EmbView v, MissWs ws, co
   if (tid == 0) {
     s_base[0] = s_n[0] ? atomicAdd(&ws.ctr[0], s_n[0]) : 0;
     s_base[1] = s_n[1] ? atomicAdd(&ws.ctr[1], s_n[1]) : 0;
-    if (s_cnt[1]) atomicAdd(&v.counters[kCtrLookups], static_cast<unsigned long long>(s_cnt[1]));
-    if (s_cnt[0]) atomicAdd(&v.counters[kCtrHits], static_cast<unsigned long long>(s_cnt[0]));
-    if (s_cnt[1] - s_cnt[0]) atomicAdd(&v.counters[kCtrMisses], static_cast<unsigned long long>(s_cnt[1] - s_cnt[0]));
-    if (s_cnt[2]) atomicAdd(&v.counters[kCtrInvalid], static_cast<unsigned long long>(s_cnt[2]));
+    if (s_cnt[1]) atomicAdd(&v.counters[ctr_index(kCtrLookups)], static_cast<unsigned long long>(s_cnt[1]));
+    if (s_cnt[0]) atomicAdd(&v.counters[ctr_index(kCtrHits)], static_cast<unsigned long long>(s_cnt[0]));
+    if (s_cnt[1] - s_cnt[0]) atomicAdd(&v.counters[ctr_index(kCtrMisses)], static_cast<unsigned long long>(s_cnt[1] - s_cnt[0]));
+    if (s_cnt[2]) atomicAdd(&v.counters[ctr_index(kCtrInvalid)], static_cast<unsigned long long>(s_cnt[2]));
   }
   __syncthreads();
   for (uint32_t k = tid; k < s_n[0]; k += 256) ws.miss_list[s_base[0] + k] = s_miss[k];
@@ -267,7 +267,8 @@ template <int PASSES>  // row_bytes / 128
 __global__ __launch_bounds__(256) void emb_probe_gather_w32(EmbView v, MissWs ws, const int64_t* __restrict__ ids,
                                                             uint32_t n, uint8_t* __restrict__ out,
                                                             uint8_t* __restrict__ hit_flags, uint32_t batch) {
-  constexpr uint32_t kPerBlock = 256;  // lookups per block: 4 waves x 8 groups x 8 rounds
+  constexpr uint32_t kRounds = 2;
+  constexpr uint32_t kPerBlock = 32 * kRounds;  // lookups per block: 4 waves x 8 groups x rounds
   __shared__ uint32_t s_miss[kPerBlock];
   __shared__ uint32_t s_n, s_base_m, s_base_d;
   __shared__ uint32_t s_cnt[3];
@@ -278,8 +279,8 @@ __global__ __launch_bounds__(256) void emb_probe_gather_w32(EmbView v, MissWs ws
   __syncthreads();
   const uint4* tags4 = reinterpret_cast<const uint4*>(v.tags);
   uint32_t n_hit = 0, n_valid = 0, n_invalid = 0;  // counted by lane 0 of each group
-#pragma unroll 2
-  for (uint32_t round = 0; round < 8; ++round) {
+#pragma unroll
+  for (uint32_t round = 0; round < kRounds; ++round) {
     const uint64_t i = static_cast<uint64_t>(blockIdx.x) * kPerBlock + (round * 4 + wave) * 8 + grp;
     const bool active = i < n;
     const int64_t id = active ? ids[i] : -1;
@@ -335,10 +336,10 @@ __global__ __launch_bounds__(256) void emb_probe_gather_w32(EmbView v, MissWs ws
     // with one lookup per row the missing lookups are also the output rows that wait
     s_base_m = s_n ? atomicAdd(&ws.ctr[0], s_n) : 0;
     s_base_d = s_n ? atomicAdd(&ws.ctr[1], s_n) : 0;
-    if (s_cnt[1]) atomicAdd(&v.counters[kCtrLookups], static_cast<unsigned long long>(s_cnt[1]));
-    if (s_cnt[0]) atomicAdd(&v.counters[kCtrHits], static_cast<unsigned long long>(s_cnt[0]));
-    if (s_cnt[1] - s_cnt[0]) atomicAdd(&v.counters[kCtrMisses], static_cast<unsigned long long>(s_cnt[1] - s_cnt[0]));
-    if (s_cnt[2]) atomicAdd(&v.counters[kCtrInvalid], static_cast<unsigned long long>(s_cnt[2]));
+    if (s_cnt[1]) atomicAdd(&v.counters[ctr_index(kCtrLookups)], static_cast<unsigned long long>(s_cnt[1]));
+    if (s_cnt[0]) atomicAdd(&v.counters[ctr_index(kCtrHits)], static_cast<unsigned long long>(s_cnt[0]));
+    if (s_cnt[1] - s_cnt[0]) atomicAdd(&v.counters[ctr_index(kCtrMisses)], static_cast<unsigned long long>(s_cnt[1] - s_cnt[0]));
+    if (s_cnt[2]) atomicAdd(&v.counters[ctr_index(kCtrInvalid)], static_cast<unsigned long long>(s_cnt[2]));
   }
   __syncthreads();
   for (uint32_t k = tid; k < s_n; k += 256) {
@@ -447,12 +448,12 @@ __global__ __launch_bounds__(256) void miss_decide(EmbView v, MissWs ws, uint32_
     const uint32_t victim_tag = __shfl(tg, half * 32 + (way >= 0 ? way : 0), kWave);
     if (act && l32 == 0) {
       ws.u_way[u] = way;
-      atomicAdd(&v.counters[kCtrUnique], 1ull);
+      atomicAdd(&v.counters[ctr_index(kCtrUnique)], 1ull);
       if (way >= 0) {
-        atomicAdd(&v.counters[kCtrInserted], 1ull);
-        if (victim_tag != kEmpty) atomicAdd(&v.counters[kCtrEvicted], 1ull);
+        atomicAdd(&v.counters[ctr_index(kCtrInserted)], 1ull);
+        if (victim_tag != kEmpty) atomicAdd(&v.counters[ctr_index(kCtrEvicted)], 1ull);
       } else {
-        atomicAdd(&v.counters[kCtrBypassed], 1ull);
+        atomicAdd(&v.counters[ctr_index(kCtrBypassed)], 1ull);
       }
     }
   }
@@ -578,8 +579,8 @@ __global__ __launch_bounds__(256) void emb_shrink_sets(EmbView v, uint32_t old_f
     const unsigned long long ev_all = __ballot(evicted);
     const uint32_t ev_m = half ? static_cast<uint32_t>(ev_all >> 32) : static_cast<uint32_t>(ev_all);
     if (act && l32 == 0) {
-      if (ev_m) atomicAdd(&v.counters[kCtrShrinkEvicted], static_cast<unsigned long long>(__popc(ev_m)));
-      if (mover_m) atomicAdd(&v.counters[kCtrShrinkMoved], static_cast<unsigned long long>(__popc(mover_m)));
+      if (ev_m) atomicAdd(&v.counters[ctr_index(kCtrShrinkEvicted)], static_cast<unsigned long long>(__popc(ev_m)));
+      if (mover_m) atomicAdd(&v.counters[ctr_index(kCtrShrinkMoved)], static_cast<unsigned long long>(__popc(mover_m)));
     }
     // row moves: destination ways are below every source way, and a destination is never
     // a later mover's source, so moving in ascending order is safe
@@ -616,7 +617,7 @@ hipError_t launch_emb_probe(const EmbView& v, const MissWs& ws, const int64_t* i
                             uint8_t* out, uint8_t* hit_flags, uint32_t batch, hipStream_t stream) {
   if (n == 0) return hipSuccess;
   if (bag == 1 && v.w_max == 32 && v.row_bytes % 128 == 0 && v.row_bytes <= 1024) {
-    const dim3 grid((n + 255) / 256), block(256);
+    const dim3 grid((n + 63) / 64), block(256);  // 64 lookups per block
     switch (v.row_bytes / 128) {
 #define RACER_W32_CASE(P) \
   case P: hipLaunchKernelGGL(emb_probe_gather_w32<P>, grid, block, 0, stream, v, ws, ids, n, out, hit_flags, batch); break;

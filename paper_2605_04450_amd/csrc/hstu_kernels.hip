@@ -167,7 +167,7 @@ struct FrontEpilogue {  // SiLU(acc + b1), split U | V | Q | K, K and V into the
     const uint32_t pos = rq.prefix_len + (row - rq.x_off);
     const int32_t page = page_tables[rq.page_table_off + pos / hd.pt];
     if (page < 0 || static_cast<uint32_t>(page) >= kv.n_pages) {
-      atomicAdd(&kv.counters[kCtrBadPages], 1ull);
+      atomicAdd(&kv.counters[ctr_index(kCtrBadPages)], 1ull);
       return;
     }
     const uint32_t head = c / hd.dh, cc = c % hd.dh, tok = pos % hd.pt;
@@ -330,7 +330,7 @@ __global__ __launch_bounds__(256) void gemm_front_bf16(HstuDims hd, uint32_t lay
       split_token(hd, pos0 + row, &pi, &ip);
       const int32_t page = page_tables[rq.page_table_off + pi];
       if (page < 0 || static_cast<uint32_t>(page) >= kv.n_pages) {
-        if (part == 0) atomicAdd(&kv.counters[kCtrBadPages], 1ull);
+        if (part == 0) atomicAdd(&kv.counters[ctr_index(kCtrBadPages)], 1ull);
         continue;
       }
       *reinterpret_cast<uint4*>(kv.base + static_cast<uint64_t>(page) * kv.page_size + koff + (static_cast<uint64_t>(ip) * 64 + part * 8) * 2) =
@@ -349,7 +349,7 @@ __global__ __launch_bounds__(256) void gemm_front_bf16(HstuDims hd, uint32_t lay
     if (whole) {
       const int32_t page = page_tables[rq.page_table_off + pi];
       if (page < 0 || static_cast<uint32_t>(page) >= kv.n_pages) {
-        if (dh == 0) atomicAdd(&kv.counters[kCtrBadPages], 1ull);
+        if (dh == 0) atomicAdd(&kv.counters[ctr_index(kCtrBadPages)], 1ull);
         continue;
       }
       uint32_t w[4];
@@ -362,7 +362,7 @@ __global__ __launch_bounds__(256) void gemm_front_bf16(HstuDims hd, uint32_t lay
         split_token(hd, pos0 + t0 + e, &pi, &ip);
         const int32_t page = page_tables[rq.page_table_off + pi];
         if (page < 0 || static_cast<uint32_t>(page) >= kv.n_pages) {
-          if (dh == 0) atomicAdd(&kv.counters[kCtrBadPages], 1ull);
+          if (dh == 0) atomicAdd(&kv.counters[ctr_index(kCtrBadPages)], 1ull);
           continue;
         }
         *reinterpret_cast<uint16_t*>(kv.base + static_cast<uint64_t>(page) * kv.page_size + voff + (static_cast<uint64_t>(dh) * hd.pt + ip) * 2) =
@@ -412,7 +412,7 @@ __global__ __launch_bounds__(256) void attention_f32(HstuDims hd, uint32_t layer
   for (uint32_t j = lane; j <= p; j += 64) {
     const int32_t page = page_tables[rq.page_table_off + j / hd.pt];
     if (page < 0 || static_cast<uint32_t>(page) >= kv.n_pages) {
-      atomicAdd(&kv.counters[kCtrBadPages], 1ull);
+      atomicAdd(&kv.counters[ctr_index(kCtrBadPages)], 1ull);
       continue;
     }
     const uint8_t* pb = kv.base + static_cast<uint64_t>(page) * kv.page_size;
@@ -580,7 +580,7 @@ __global__ __launch_bounds__(256, NQB == 1 ? 4 : 2) void attention_bf16_mfma(Hst
     for (uint32_t i = tid; i <= page_last - page0 && i < kAttnMaxItemPages; i += 256) {
       int32_t pg = page_tables[rq.page_table_off + page0 + i];
       if (pg < 0 || static_cast<uint32_t>(pg) >= kv.n_pages) {
-        atomicAdd(&kv.counters[kCtrBadPages], 1ull);
+        atomicAdd(&kv.counters[ctr_index(kCtrBadPages)], 1ull);
         pg = -1;
       }
       sm.pages[i] = pg;

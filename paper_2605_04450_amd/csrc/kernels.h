@@ -12,6 +12,13 @@ enum Counter : int {
   kCtrInvalid, kCtrShrinkEvicted, kCtrShrinkMoved, kCtrBadPages, kCtrCount
 };
 
+// The counters exist in kCtrShards copies; a block adds to the copy chosen by its index so that
+// thousands of blocks do not serialise on one address.  pool_stats adds the copies up.
+constexpr int kCtrShards = 64;
+#if defined(__HIPCC__)
+__device__ __forceinline__ int ctr_index(int counter) { return static_cast<int>(blockIdx.x & (kCtrShards - 1)) * kCtrCount + counter; }
+#endif
+
 // Everything a kernel needs to find a cache set, its ways and its rows.
 // Way layer w of the cache = slot w of every set = `layer_pages` consecutive logical EMB
 // pages; slot (w, s) lives in logical page w*layer_pages + s/spp at offset s%spp.

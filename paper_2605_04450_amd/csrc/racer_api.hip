@@ -259,7 +259,7 @@ int32_t pool_create(void* dev_base, uint64_t bytes, uint64_t page_size, const ra
     const uint64_t n_tags = sets * cfg->w_max;
     if ((rc = dev_alloc(&p->d_tags, n_tags, false)) || (rc = dev_alloc(&p->d_stamps, n_tags, true)) ||
         (rc = dev_alloc(&p->d_emb_pages, n_pages, true)) ||
-        (rc = dev_alloc(&p->d_counters, racer::kCtrCount, true))) {
+        (rc = dev_alloc(&p->d_counters, racer::kCtrCount * racer::kCtrShards, true))) {
       pool_destroy(p);
       return rc;
     }
@@ -338,8 +338,11 @@ int32_t pool_stats(racer_pool_t* p, racer_pool_stats* out) {
   std::memset(out, 0, sizeof(*out));
   if (p->device) {
     HIP_TRY(hipStreamSynchronize(p->last_stream));
-    unsigned long long c[racer::kCtrCount];
-    HIP_TRY(hipMemcpy(c, p->d_counters, sizeof(c), hipMemcpyDeviceToHost));
+    unsigned long long shards[racer::kCtrShards][racer::kCtrCount];
+    HIP_TRY(hipMemcpy(shards, p->d_counters, sizeof(shards), hipMemcpyDeviceToHost));
+    unsigned long long c[racer::kCtrCount] = {};
+    for (int sh = 0; sh < racer::kCtrShards; ++sh)
+      for (int k = 0; k < racer::kCtrCount; ++k) c[k] += shards[sh][k];
     out->lookups = c[racer::kCtrLookups];
     out->hits = c[racer::kCtrHits];
     out->misses = c[racer::kCtrMisses];
