@@ -200,13 +200,19 @@ class Pool:
         return lib().orc_kv_seq_release(self._h, key)
 
     def emb_lookup(self, ids, table, bag=1, want_out=True):
-        """table: [rows][d] float32, or uint16 holding bf16 bit patterns. Returns (rc, out, hit)."""
+        """table: [rows][d] float32, or uint16 holding bf16 bit patterns; with want_out=False it may be
+        just (rows, d, dtype), since no row is read then. Returns (rc, out, hit)."""
         ids = _c(ids, np.int64)
-        assert table.dtype in (np.float32, np.uint16) and table.ndim == 2 and table.flags.c_contiguous
-        elem = 0 if table.dtype == np.float32 else 1
         n = ids.size
-        rows, d = table.shape
-        out = np.zeros((n // bag if bag else 0, d), dtype=table.dtype) if want_out else None
+        if isinstance(table, tuple):
+            assert not want_out
+            rows, d, dtype = table
+            table = None
+        else:
+            assert table.dtype in (np.float32, np.uint16) and table.ndim == 2 and table.flags.c_contiguous
+            rows, d, dtype = table.shape[0], table.shape[1], table.dtype
+        elem = 0 if dtype == np.float32 else 1
+        out = np.zeros((n // bag if bag else 0, d), dtype=dtype) if want_out else None
         hit = np.zeros(n, dtype=np.uint8)
         rc = lib().orc_emb_lookup(self._h, _ptr(ids), n, bag, _ptr(table), rows, d, elem, _ptr(out), _ptr(hit))
         return rc, out, hit
