@@ -35,6 +35,18 @@ CONFIGS = {
 }
 
 
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    try:
+        for line in open(path):
+            if line.startswith("traffic.%s.%s=" % (kernel, workload)):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def build_workload(c, torch, Hn, B, synth):
     dev = Hn.DEV
     L, d, H, bf16, pt = c["L"], c["d"], c["H"], c["bf16"], c["pt"]
@@ -136,6 +148,9 @@ def main():
     ap.add_argument("--config", default="mid", choices=sorted(CONFIGS))
     ap.add_argument("--cpu-tokens", type=int, default=None, help="token budget of the oracle sample")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--copy-calib-mb", type=int, default=0,
+                    help="after the timed region, run one plain device copy of this many MiB (a kernel of known "
+                         "traffic against which HBM byte counters of a profiler run are scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported (every figure is the one "
@@ -168,6 +183,12 @@ def main():
     prof = B.racer_prof_read(pool.h)
     B.racer_prof_enable(pool.h, 0)
     st1 = pool.stats()
+    if args.copy_calib_mb:
+        src = torch.empty(args.copy_calib_mb << 20, dtype=torch.uint8, device=Hn.DEV)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     ms_per_step = dt * 1e3 / args.steps
     N, d, L, H = wl["N"], c["d"], c["L"], c["H"]
     lens = wl["lens"].astype(np.float64)
@@ -196,7 +217,8 @@ def main():
                        "hit_rate": hits / max(lookups, 1)},
         "roofline": {"kernel": "attention_bf16_mfma" if c["bf16"] else "attention_f32", "bound": "mfma",
                      "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": attn_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": attn_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": measured_traffic("attention_bf16_mfma", args.config) if c["bf16"] else None,
                      "flop_per_launch": attn_flop, "ms_per_launch": attn_ms},
         "kernels": kernels,
     }

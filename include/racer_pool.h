@@ -202,7 +202,8 @@ int32_t hstu_attn_paged(racer_pool_t* pool, racer_hstu_t* model, uint32_t layer,
 #define RACER_PROF_GEMM_FRONT 3
 #define RACER_PROF_ATTENTION 4
 #define RACER_PROF_GEMM_BACK 5
-#define RACER_PROF_KINDS 6
+#define RACER_PROF_ATTN_REDUCE 6 /* sum of the partial outputs of split attention items */
+#define RACER_PROF_KINDS 7
 typedef struct {
   double ms[RACER_PROF_KINDS];
   uint64_t launches[RACER_PROF_KINDS];

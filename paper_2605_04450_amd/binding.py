@@ -22,11 +22,11 @@ EXPORTS = [
     "kv_seq_release", "emb_lookup", "hstu_model_create", "hstu_model_destroy", "hstu_step",
     "hstu_attn_paged", "racer_last_error", "racer_prof_enable", "racer_prof_read",
 ]
-PROF_KINDS = ("emb_gather", "emb_miss", "layernorm", "gemm_front", "attention", "gemm_back")
+PROF_KINDS = ("emb_gather", "emb_miss", "layernorm", "gemm_front", "attention", "gemm_back", "attn_reduce")
 
 
 class Prof(C.Structure):
-    _fields_ = [("ms", C.c_double * 6), ("launches", C.c_uint64 * 6)]
+    _fields_ = [("ms", C.c_double * 7), ("launches", C.c_uint64 * 7)]
 
 
 class PoolCfg(C.Structure):

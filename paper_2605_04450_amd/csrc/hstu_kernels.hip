@@ -948,15 +948,19 @@ hipError_t launch_attention(const HstuDims& hd, uint32_t layer, const void* q, c
       hipLaunchKernelGGL(attention_bf16_mfma<2>, dim3(sl.n_items * hd.H), dim3(256), 0, stream, hd, layer,
                          static_cast<const uint16_t*>(q), pos, time, kv, sl.reqs, sl.items, sl.partials, page_tables,
                          reinterpret_cast<const long long*>(ts), static_cast<uint16_t*>(o));
-    if (sl.n_groups)
-      hipLaunchKernelGGL(attention_reduce, dim3(sl.n_groups * hd.H), dim3(256), 0, stream, hd, sl.q_block, sl.reqs,
-                         sl.groups, sl.partials, static_cast<uint16_t*>(o));
   } else {
     const uint32_t items = sl.N * hd.H;
     hipLaunchKernelGGL(attention_f32, dim3((items + 3) / 4), dim3(256), 0, stream, hd, layer,
                        static_cast<const float*>(q), pos, time, kv, sl.reqs, sl.row_req, sl.N, page_tables,
                        reinterpret_cast<const long long*>(ts), static_cast<float*>(o));
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_reduce(const HstuDims& hd, const StepLists& sl, void* o, hipStream_t stream) {
+  if (hd.elem != 1 || sl.n_groups == 0) return hipSuccess;
+  hipLaunchKernelGGL(attention_reduce, dim3(sl.n_groups * hd.H), dim3(256), 0, stream, hd, sl.q_block, sl.reqs,
+                     sl.groups, sl.partials, static_cast<uint16_t*>(o));
   return hipGetLastError();
 }
 

@@ -137,6 +137,8 @@ hipError_t launch_gemm_back(const HstuDims& hd, const void* g, const void* w2t, 
 hipError_t launch_attention(const HstuDims& hd, uint32_t layer, const void* q, const float* pos,
                             const float* time, const KvView& kv, const StepLists& sl,
                             const int32_t* page_tables, const int64_t* ts, void* o, hipStream_t stream);
+// adds up the fp32 partials of split attention items (no-op when nothing was split)
+hipError_t launch_attention_reduce(const HstuDims& hd, const StepLists& sl, void* o, hipStream_t stream);
 // bf16 models: pos and time must be the tables multiplied by log2(e) (launch_scale_bias), and
 // q must already be multiplied by log2(e) (launch_gemm_front stores it that way)
 hipError_t launch_scale_bias(const float* in, float* out, uint64_t n, hipStream_t stream);

@@ -690,6 +690,10 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
                                       bf16 ? m->time_s : static_cast<const float*>(m->w.time), ctx.kv, ctx.sl,
                                       page_tables, ts, o, stream));
     }
+    if (ctx.sl.n_groups) {
+      ProfScope t(p, RACER_PROF_ATTN_REDUCE, stream);
+      HIP_TRY(racer::launch_attention_reduce(ctx.hd, ctx.sl, o, stream));
+    }
     {
       ProfScope t(p, RACER_PROF_LAYERNORM, stream);
       HIP_TRY(racer::launch_layernorm(ctx.hd, o, ln2_g, ln2_b, u, xn, N, stream));
@@ -728,6 +732,10 @@ int32_t hstu_attn_paged(racer_pool_t* p, racer_hstu_t* m, uint32_t layer, const 
     HIP_TRY(racer::launch_attention(ctx.hd, layer, q, bf16 ? m->pos_s : static_cast<const float*>(m->w.pos),
                                     bf16 ? m->time_s : static_cast<const float*>(m->w.time), ctx.kv, ctx.sl,
                                     page_tables, ts, o, stream));
+  }
+  if (ctx.sl.n_groups) {
+    ProfScope t(p, RACER_PROF_ATTN_REDUCE, stream);
+    HIP_TRY(racer::launch_attention_reduce(ctx.hd, ctx.sl, o, stream));
   }
   return RACER_OK;
 }
