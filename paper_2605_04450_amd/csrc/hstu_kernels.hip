@@ -505,7 +505,7 @@ __device__ __forceinline__ float silu_log2(float y) {
 // NQB = 32-query groups per wavefront: 1 -> 128 queries per block and four resident blocks per CU,
 // 2 -> 256 queries per block (each staged tile serves twice the queries) and two resident blocks.
 template <int NQB>
-__global__ __launch_bounds__(256, NQB == 1 ? 4 : 2) void attention_bf16_mfma(HstuDims hd, uint32_t layer, const uint16_t* __restrict__ q,
+__global__ __launch_bounds__(256, NQB == 1 ? 3 : 2) void attention_bf16_mfma(HstuDims hd, uint32_t layer, const uint16_t* __restrict__ q,
                                                               const float* __restrict__ pos,
                                                               const float* __restrict__ time, KvView kv,
                                                               const ReqDev* __restrict__ reqs,
@@ -695,20 +695,17 @@ __global__ __launch_bounds__(256, NQB == 1 ? 4 : 2) void attention_bf16_mfma(Hst
     __syncthreads();  // tile kt is visible
     if (kt + 1 < kt_end) fetch(kt + 1);  // its global loads fly while this tile is consumed
 
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb) {
-      const uint32_t kb = j0 + 32 * sb;
-      if (!grp_active[0] || kb > grp_last[NQB - 1]) continue;  // nothing of this sub-block is visible to the wave
+    {
       // operands are read from LDS right where they are consumed: holding all of them across
       // the epilogue would push the kernel past 256 registers
-      auto k_frag = [&](int st) {
+      auto k_frag = [&](int sb, int st) {
         return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&tl.Ks[32 * sb + krow][16 * st + 8 * g]));
       };
-      auto v_frag = [&](int s2, int db) {
+      auto v_frag = [&](int sb, int s2, int db) {
         return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&tl.Vs[32 * db + li][32 * sb + 16 * s2 + 8 * g]));
       };
       // S^T = K Q^T on top of the positional bias: lane's window entries m0 .. m0+7 and m0+16 .. m0+23
-      auto scores_begin = [&](int qb) {
+      auto scores_begin = [&](int qb, int sb) {
         const uint32_t m0 = (kQ - 1) - ql[qb] + 32 * sb + 8 * g;
         const float* pw = &tl.pos[m0 & 3][4 + (m0 & ~3u)];
         const float4 w0 = *reinterpret_cast<const float4*>(pw), w1 = *reinterpret_cast<const float4*>(pw + 4);
@@ -722,7 +719,8 @@ __global__ __launch_bounds__(256, NQB == 1 ? 4 : 2) void attention_bf16_mfma(Hst
       };
       // bias, SiLU, mask -> bf16 pairs.  sacc[e]: key kb + 16*(e/8) + 8*g + e%8, query li of group qb;
       // y = (q.k + pos) * log2 e
-      auto epilogue = [&](int qb, const f32x16& sacc, uint32_t pk[8]) {
+      auto epilogue = [&](int qb, int sb, const f32x16& sacc, uint32_t pk[8]) {
+        const uint32_t kb = j0 + 32 * sb;
         const bool diag = kb + 31 > grp_first[qb];
         int mode = 2;  // 0: one time bias for the block, 1: two adjacent buckets, 2: bucket per score (+ mask)
         float c_lo = 0.0f, c_hi = 0.0f;
@@ -772,40 +770,60 @@ __global__ __launch_bounds__(256, NQB == 1 ? 4 : 2) void attention_bf16_mfma(Hst
         }
       };
       // O^T += V^T P^T; the P^T operand of step s2 = elements 8*s2 .. 8*s2+7: keys kb + 16*s2 + 8*g + 0..7
-      auto accumulate = [&](int qb, const uint32_t pk[8]) {
+      auto accumulate = [&](int qb, int sb, const uint32_t pk[8]) {
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
           const bf16x8 pf = __builtin_bit_cast(bf16x8, make_uint4(pk[4 * s2], pk[4 * s2 + 1], pk[4 * s2 + 2], pk[4 * s2 + 3]));
 #pragma unroll
           for (int db = 0; db < 2; ++db)
-            oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag(s2, db), pf, oacc[qb][db], 0, 0, 0);
+            oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag(sb, s2, db), pf, oacc[qb][db], 0, 0, 0);
         }
       };
-      if (NQB == 2 && grp_active[NQB - 1] && kb <= grp_last[0]) {
-        // both query groups see the sub-block: their two product chains are issued interleaved,
-        // and each group's second product runs while the other group's epilogue executes
-        f32x16 s0 = scores_begin(0), s1 = scores_begin(NQB - 1);
+      // which (query group, sub-block) pairs hold at least one visible (query, key) pair
+      auto visible = [&](int qb, int sb) { return grp_active[qb] && j0 + 32 * sb <= grp_last[qb]; };
+      if (NQB == 1 && visible(0, 1)) {
+        // both sub-blocks are visible: the two score chains are issued interleaved, and each
+        // sub-block's second product runs while the other's epilogue executes
+        f32x16 s0 = scores_begin(0, 0), s1 = scores_begin(0, 1);
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-          const bf16x8 kf = k_frag(st);
-          s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][st], s0, 0, 0, 0);
-          s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[NQB - 1][st], s1, 0, 0, 0);
+          s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(0, st), qf[0][st], s0, 0, 0, 0);
+          s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(1, st), qf[0][st], s1, 0, 0, 0);
         }
         uint32_t pk0[8], pk1[8];
-        epilogue(0, s0, pk0);
-        accumulate(0, pk0);
-        epilogue(NQB - 1, s1, pk1);
-        accumulate(NQB - 1, pk1);
+        epilogue(0, 0, s0, pk0);
+        accumulate(0, 0, pk0);
+        epilogue(0, 1, s1, pk1);
+        accumulate(0, 1, pk1);
       } else {
 #pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-          if (!grp_active[qb] || kb > grp_last[qb]) continue;
-          f32x16 s0 = scores_begin(qb);
+        for (int sb = 0; sb < 2; ++sb) {
+          if (NQB == 2 && visible(0, sb) && visible(NQB - 1, sb) && j0 + 32 * sb <= grp_last[0]) {
+            // both query groups see the sub-block: same interleaving over the groups
+            f32x16 s0 = scores_begin(0, sb), s1 = scores_begin(NQB - 1, sb);
 #pragma unroll
-          for (int st = 0; st < 4; ++st) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(st), qf[qb][st], s0, 0, 0, 0);
-          uint32_t pk0[8];
-          epilogue(qb, s0, pk0);
-          accumulate(qb, pk0);
+            for (int st = 0; st < 4; ++st) {
+              const bf16x8 kf = k_frag(sb, st);
+              s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][st], s0, 0, 0, 0);
+              s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[NQB - 1][st], s1, 0, 0, 0);
+            }
+            uint32_t pk0[8], pk1[8];
+            epilogue(0, sb, s0, pk0);
+            accumulate(0, sb, pk0);
+            epilogue(NQB - 1, sb, s1, pk1);
+            accumulate(NQB - 1, sb, pk1);
+          } else {
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb) {
+              if (!visible(qb, sb)) continue;
+              f32x16 s0 = scores_begin(qb, sb);
+#pragma unroll
+              for (int st = 0; st < 4; ++st) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(sb, st), qf[qb][st], s0, 0, 0, 0);
+              uint32_t pk0[8];
+              epilogue(qb, sb, s0, pk0);
+              accumulate(qb, sb, pk0);
+            }
+          }
         }
       }
     }
