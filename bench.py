@@ -223,7 +223,7 @@ def main():
         "kernels": kernels,
     }
     if not args.no_cpu:
-        budget = args.cpu_tokens or (1024 if args.config == "tiny" else 6000)
+        budget = args.cpu_tokens or (1024 if args.config == "tiny" else 56000)
         cb, take, ref = cpu_baseline(c, wl, synth, budget)
         result["cpu_baseline"] = cb
     print(json.dumps(result))

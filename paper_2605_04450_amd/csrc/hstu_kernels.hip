@@ -63,8 +63,10 @@ __device__ __forceinline__ void split_token(const HstuDims& hd, uint32_t j, uint
 }
 
 // ---------------------------------------------------------------------------------------
-// LayerNorm over d (optionally times a gate row), one wavefront per row, two-pass in fp32.
-// A lane owns chunks of 8 consecutive elements (16-byte accesses for bf16), d <= 1024.
+// LayerNorm over d (optionally times a gate row), two-pass in fp32.  A row is owned by LPR
+// consecutive lanes of a wavefront (64 / LPR rows per wavefront, LPR chosen so that every
+// lane has work); a lane holds KC chunks of 8 consecutive elements (16-byte accesses for
+// bf16), d <= 1024.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ void load8(const float* p, float v[8]) {
   const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
@@ -92,51 +94,62 @@ __device__ __forceinline__ void store8(bf16_t* p, const float v[8]) {
   *reinterpret_cast<uint4*>(p) = a;
 }
 
-template <typename T>
+template <int LPR>
+__device__ __forceinline__ float group_sum(float v) {  // sum over the LPR lanes that share a row
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+template <typename T, int LPR, int KC>
 __global__ __launch_bounds__(256) void layernorm_rows(const T* __restrict__ x, const float* __restrict__ g,
                                                       const float* __restrict__ b, const T* __restrict__ gate,
                                                       T* __restrict__ y, uint32_t N, uint32_t d, float eps) {
-  const uint32_t lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= N) return;
+  const uint32_t sub = threadIdx.x % LPR;
+  const uint32_t row = blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
+  const bool row_ok = row < N;  // lanes of a missing row still take part in the shuffles
   const uint32_t chunks = d / 8;
-  float v[2][8];
+  const uint64_t base = static_cast<uint64_t>(row_ok ? row : 0) * d;
+  float v[KC][8], gt[KC][8];
+#pragma unroll
+  for (int k = 0; k < KC; ++k) {
+    const uint32_t c = sub + LPR * k;
+    const bool on = row_ok && c < chunks;
+    if (on) load8(x + base + 8 * c, v[k]);
+    if (on && gate) load8(gate + base + 8 * c, gt[k]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (!on) v[k][e] = 0.0f;
+  }
   float s = 0.0f;
 #pragma unroll
-  for (int k = 0; k < 2; ++k) {
-    const uint32_t c = lane + 64 * k;
-    if (c < chunks) load8(x + static_cast<uint64_t>(row) * d + 8 * c, v[k]);
+  for (int k = 0; k < KC; ++k)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      if (c >= chunks) v[k][e] = 0.0f;
-      s += v[k][e];
-    }
-  }
-  const float mean = wave_sum(s) / d;
+    for (int e = 0; e < 8; ++e) s += v[k][e];
+  const float mean = group_sum<LPR>(s) / d;
   float q = 0.0f;
 #pragma unroll
-  for (int k = 0; k < 2; ++k)
+  for (int k = 0; k < KC; ++k)
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const float dv = (lane + 64 * k < chunks) ? v[k][e] - mean : 0.0f;
+      const float dv = (sub + LPR * k < chunks) ? v[k][e] - mean : 0.0f;
       q += dv * dv;
     }
-  const float rstd = 1.0f / sqrtf(wave_sum(q) / d + eps);
+  const float rstd = 1.0f / sqrtf(group_sum<LPR>(q) / d + eps);
 #pragma unroll
-  for (int k = 0; k < 2; ++k) {
-    const uint32_t c = lane + 64 * k;
-    if (c >= chunks) continue;
+  for (int k = 0; k < KC; ++k) {
+    const uint32_t c = sub + LPR * k;
+    if (!row_ok || c >= chunks) continue;
     float gg[8], bb[8], o[8];
     load8(g + 8 * c, gg);
     load8(b + 8 * c, bb);
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = (v[k][e] - mean) * rstd * gg[e] + bb[e];
     if (gate) {
-      float gt[8];
-      load8(gate + static_cast<uint64_t>(row) * d + 8 * c, gt);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] *= gt[e];
+      for (int e = 0; e < 8; ++e) o[e] *= gt[k][e];
     }
-    store8(y + static_cast<uint64_t>(row) * d + 8 * c, o);
+    store8(y + base + 8 * c, o);
   }
 }
 
@@ -479,8 +492,9 @@ struct AttnTile {  // one staged key tile
 };
 
 struct AttnShared {
-  AttnTile tile;  // the next tile travels in registers while this one is consumed
+  AttnTile tile[2];  // tile k is consumed from one half while tile k+1 is written into the other
   float time[64];
+  float rtime[32];   // rtime[c] = time bias of a gap with c leading zero bits (32-bit gaps, n_time <= 32)
   int32_t pages[kAttnMaxItemPages];  // page ids of the item's key range (-1: outside the pool)
 };
 
@@ -528,6 +542,10 @@ __global__ __launch_bounds__(256, NQB == 1 ? 3 : 2) void attention_bf16_mfma(Hst
   const long long span = tsr[S - 1] - ts_base;
   const bool fast = hd.n_time <= 32 && span >= 0 && span < (1ll << 31);
   if (tid < 64) sm.time[tid] = tid < hd.n_time ? time[(static_cast<uint64_t>(layer) * hd.H + h) * hd.n_time + tid] : 0.0f;
+  if (tid >= 64 && tid < 96) {
+    const uint32_t bkt = 95 - tid;  // floor(log2(gap)) of a gap with tid - 64 leading zeros
+    sm.rtime[tid - 64] = time[(static_cast<uint64_t>(layer) * hd.H + h) * hd.n_time + (bkt < hd.n_time - 1 ? bkt : hd.n_time - 1)];
+  }
   const float* pos_h = pos + (static_cast<uint64_t>(layer) * hd.H + h) * hd.n_pos;
 
   // per 32-query group qb of this wavefront
@@ -686,14 +704,37 @@ __global__ __launch_bounds__(256, NQB == 1 ? 3 : 2) void attention_bf16_mfma(Hst
     if (tid < 64) t.tk[tid] = treg;
   };
 
-  fetch(kt_begin);
-  for (uint32_t kt = kt_begin; kt < kt_end; ++kt) {
+  // first and last key timestamp of the two 32-key halves of a tile, through the scalar unit
+  // (read-only), one tile ahead; indices are clamped to the sequence
+  auto tile_times = [&](uint32_t kt, uint32_t out[4]) {
     const uint32_t j0 = kt * 64;
-    AttnTile& tl = sm.tile;
-    if (kt != kt_begin) __syncthreads();  // every wave has finished tile kt-1
-    commit(tl);
-    __syncthreads();  // tile kt is visible
-    if (kt + 1 < kt_end) fetch(kt + 1);  // its global loads fly while this tile is consumed
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t j = j0 + 32 * (k >> 1) + 31 * (k & 1);
+      out[k] = static_cast<uint32_t>(tsr[j < S ? j : S - 1] - ts_base);
+    }
+  };
+  uint32_t tkb[4], tkb_next[4] = {0, 0, 0, 0};
+  fetch(kt_begin);
+  tile_times(kt_begin, tkb);
+  commit(sm.tile[0]);
+  if (kt_begin + 1 < kt_end) fetch(kt_begin + 1);
+  uint32_t cur = 0;
+  for (uint32_t kt = kt_begin; kt < kt_end; ++kt, cur ^= 1) {
+    const uint32_t j0 = kt * 64;
+    AttnTile& tl = sm.tile[cur];
+    // one barrier per tile: tile kt is visible, and every wave is done with tile kt-1, whose
+    // half now takes tile kt+1 (in registers since the previous iteration)
+    __syncthreads();
+    if (kt != kt_begin) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) tkb[k] = tkb_next[k];
+    }
+    if (kt + 1 < kt_end) {
+      commit(sm.tile[cur ^ 1]);
+      tile_times(kt + 1, tkb_next);
+      if (kt + 2 < kt_end) fetch(kt + 2);  // its global loads fly while this tile is consumed
+    }
 
     {
       // operands are read from LDS right where they are consumed: holding all of them across
@@ -726,8 +767,7 @@ __global__ __launch_bounds__(256, NQB == 1 ? 3 : 2) void attention_bf16_mfma(Hst
         float c_lo = 0.0f, c_hi = 0.0f;
         uint32_t thr = 0;
         if (fast && !diag) {
-          const uint32_t tk_first = __builtin_amdgcn_readfirstlane(tl.tk[32 * sb]);
-          const uint32_t tk_last = __builtin_amdgcn_readfirstlane(tl.tk[32 * sb + 31]);
+          const uint32_t tk_first = tkb[2 * sb], tk_last = tkb[2 * sb + 1];
           const uint32_t bmin = bucket_u32(tq_first[qb] - tk_last, hd.n_time);
           const uint32_t bmax = bucket_u32(tq_last[qb] - tk_first, hd.n_time);
           c_lo = sm.time[bmin];
@@ -743,31 +783,56 @@ __global__ __launch_bounds__(256, NQB == 1 ? 3 : 2) void attention_bf16_mfma(Hst
 #pragma unroll
           for (int e = 0; e < 16; e += 2)
             pk[e >> 1] = pack_bf16x2(silu_log2(sacc[e] + c_lo), silu_log2(sacc[e + 1] + c_lo));
-        } else if (mode == 1) {
-          const uint32_t* tkp = &tl.tk[32 * sb + 8 * g];
-          float a[16];
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const uint32_t gap = tq[qb] - tkp[16 * (e / 8) + (e % 8)];
-            a[e] = silu_log2(sacc[e] + (gap >= thr ? c_hi : c_lo));
-          }
-#pragma unroll
-          for (int e = 0; e < 16; e += 2) pk[e >> 1] = pack_bf16x2(a[e], a[e + 1]);
-        } else {
+          return;
+        }
+        if (fast) {
+          // eight scores at a time: the lane's key timestamps (all below 2^31) come as two 16-byte reads
+          const uint4* tkp = reinterpret_cast<const uint4*>(&tl.tk[32 * sb + 8 * g]);
+          const int32_t lim_t = tq[qb] >= thr ? static_cast<int32_t>(tq[qb] - thr) : -1;
           const int lim = static_cast<int>(p[qb]) - static_cast<int>(kb) - 8 * static_cast<int>(g);  // visible: key offset <= lim
-          float a[16];
+#pragma unroll
+          for (int hf = 0; hf < 2; ++hf) {
+            const uint4 t0 = tkp[4 * hf], t1 = tkp[4 * hf + 1];
+            const uint32_t tkl[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
+            float a[8];
+            if (mode == 1) {
+              // gap >= thr  <=>  key time <= query time - thr (never, if that is negative)
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                a[e] = silu_log2(sacc[8 * hf + e] + (static_cast<int32_t>(tkl[e]) <= lim_t ? c_hi : c_lo));
+            } else {
+              // bucket per score through the table indexed by the gap's leading zero count; a key after
+              // the query gives a wrapped gap, whose (valid) table entry the causal select discards
+#pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                const uint32_t gap = tq[qb] - tkl[e];
+                a[e] = silu_log2(sacc[8 * hf + e] + sm.rtime[__clz(static_cast<int>(gap > 1 ? gap : 1))]);
+              }
+              if (diag) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) a[e] = 16 * hf + e <= lim ? a[e] : 0.0f;
+              }
+            }
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) pk[4 * hf + (e >> 1)] = pack_bf16x2(a[e], a[e + 1]);
+          }
+          return;
+        }
+        float a[16];
+        {
+          // 64-bit gaps (requests spanning 2^31 s or more, or more than 32 buckets)
+          const int lim = static_cast<int>(p[qb]) - static_cast<int>(kb) - 8 * static_cast<int>(g);
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
             const int off = 16 * (e / 8) + (e % 8);
             const uint32_t jl = 32 * sb + off + 8 * g;
-            const uint32_t bkt = fast ? bucket_u32(tq[qb] - tl.tk[jl], hd.n_time)
-                                      : time_bucket(ts_q[qb] - (j0 + jl < S ? tsr[j0 + jl] : ts_base), hd.n_time);
+            const uint32_t bkt = time_bucket(ts_q[qb] - (j0 + jl < S ? tsr[j0 + jl] : ts_base), hd.n_time);
             const float v = silu_log2(sacc[e] + sm.time[bkt]);
             a[e] = off <= lim ? v : 0.0f;
           }
-#pragma unroll
-          for (int e = 0; e < 16; e += 2) pk[e >> 1] = pack_bf16x2(a[e], a[e + 1]);
         }
+#pragma unroll
+        for (int e = 0; e < 16; e += 2) pk[e >> 1] = pack_bf16x2(a[e], a[e + 1]);
       };
       // O^T += V^T P^T; the P^T operand of step s2 = elements 8*s2 .. 8*s2+7: keys kb + 16*s2 + 8*g + 0..7
       auto accumulate = [&](int qb, int sb, const uint32_t pk[8]) {
@@ -907,16 +972,30 @@ __global__ void transpose_kernel(const T* __restrict__ w, T* __restrict__ wt, ui
 
 }  // namespace
 
+template <typename T>
+static void layernorm_dispatch(const HstuDims& hd, const void* x, const float* g, const float* b, const void* gate,
+                               void* y, uint32_t N, hipStream_t stream) {
+  const T* xs = static_cast<const T*>(x);
+  const T* gs = static_cast<const T*>(gate);
+  T* ys = static_cast<T*>(y);
+  const uint32_t chunks = hd.d / 8;
+  const dim3 block(256);
+#define RACER_LN(LPR, KC)                                                                                   \
+  hipLaunchKernelGGL((layernorm_rows<T, LPR, KC>), dim3((N + 256 / LPR - 1) / (256 / LPR)), block, 0, stream, \
+                     xs, g, b, gs, ys, N, hd.d, hd.eps)
+  if (chunks <= 8) RACER_LN(8, 1);
+  else if (chunks <= 16) RACER_LN(16, 1);
+  else if (chunks <= 32) RACER_LN(32, 1);
+  else if (chunks <= 64) RACER_LN(64, 1);
+  else RACER_LN(64, 2);
+#undef RACER_LN
+}
+
 hipError_t launch_layernorm(const HstuDims& hd, const void* x, const float* g, const float* b, const void* gate,
                             void* y, uint32_t N, hipStream_t stream) {
   if (N == 0) return hipSuccess;
-  const dim3 grid((N + 3) / 4), block(256);
-  if (hd.elem == 1)
-    hipLaunchKernelGGL(layernorm_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t*>(x), g, b,
-                       static_cast<const bf16_t*>(gate), static_cast<bf16_t*>(y), N, hd.d, hd.eps);
-  else
-    hipLaunchKernelGGL(layernorm_rows<float>, grid, block, 0, stream, static_cast<const float*>(x), g, b,
-                       static_cast<const float*>(gate), static_cast<float*>(y), N, hd.d, hd.eps);
+  if (hd.elem == 1) layernorm_dispatch<bf16_t>(hd, x, g, b, gate, y, N, stream);
+  else layernorm_dispatch<float>(hd, x, g, b, gate, y, N, stream);
   return hipGetLastError();
 }
 

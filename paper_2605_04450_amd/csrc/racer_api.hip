@@ -5,7 +5,6 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -518,8 +517,7 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   // many more key tiles than early ones, and one long request would otherwise set the
   // kernel's duration.  Key ranges are therefore cut into chunks of at most `chunk` tiles,
   // sized so that about two items per resident block slot exist, and launched largest first.
-  uint32_t q_block = 128;
-  if (const char* ev = std::getenv("RACER_EXP_QBLOCK")) q_block = static_cast<uint32_t>(std::atoi(ev)) == 256 ? 256 : 128;
+  const uint32_t q_block = 128;
   struct QTile { uint32_t req, qt, n_kt; };
   std::vector<QTile> qtiles;
   uint64_t visits = 0;
@@ -533,7 +531,6 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   }
   const uint64_t block_slots = q_block == 128 ? 1024 : 512;  // 256 CUs x resident blocks
   uint32_t chunk = static_cast<uint32_t>(std::max<uint64_t>(8, (visits * c.H + 2 * block_slots - 1) / (2 * block_slots)));
-  if (const char* ev = std::getenv("RACER_EXP_CHUNK")) chunk = static_cast<uint32_t>(std::atoi(ev));
   // an item's slice of the page table must fit the kernel's LDS copy
   const uint32_t chunk_cap = static_cast<uint32_t>((static_cast<uint64_t>(racer::kAttnMaxItemPages) - 2) * c.page_tokens / 64);
   chunk = std::min(chunk, std::max<uint32_t>(1, chunk_cap));
