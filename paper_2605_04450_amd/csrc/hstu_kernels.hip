@@ -460,8 +460,8 @@ __global__ __launch_bounds__(256) void attention_f32(HstuDims hd, uint32_t layer
 // and 16 keys), applies bias, SiLU and the causal mask in registers, and feeds the bf16
 // result straight back as the second operand of O^T += V^T P^T: the accumulator layout of
 // the first product is the operand layout of the second, so the scores never leave
-// registers.  K rows are fed to the first product in a permuted order (bits 2 and 3 of the
-// row index swapped) so that the 8 keys a lane holds per contraction step are consecutive
+// registers.  K rows are kept in LDS in a permuted order (bits 2 and 3 of the key
+// index swapped) so that the 8 keys a lane holds per contraction step are consecutive
 // and the matching V^T operand is one 16-byte LDS read.
 //
 // The epilogue is the binding unit (16 scores per lane against 8 MFMAs), so it is pared
@@ -488,7 +488,9 @@ struct AttnTile {  // one staged key tile
   uint16_t Ks[64][64 + kLdsPad];
   uint16_t Vs[64][64 + kLdsPad];
   uint32_t tk[64];             // key timestamps relative to the request's first one
-  float pos[4][kPosWinMax + 4];  // copy s holds window entry x at [s][4 + x - s]
+  // copy s holds window entry x at [s][4 + x - s]; a copy is 32 bytes (mod 128) long, which spreads the
+  // 16-byte reads of eight neighbouring lanes (two per copy) over all LDS banks
+  float pos[4][kPosWinMax + 8];
 };
 
 struct AttnShared {
@@ -516,14 +518,14 @@ __device__ __forceinline__ float silu_log2(float y) {
   return y * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-y));
 }
 
-// NQB = 32-query groups per wavefront: 1 -> 128 queries per block and four resident blocks per CU,
-// 2 -> 256 queries per block (each staged tile serves twice the queries) and two resident blocks.
+// NQB = 32-query groups per wavefront (1: 128 queries per block, three resident blocks per CU).
 template <int NQB>
 __global__ __launch_bounds__(256, NQB == 1 ? 3 : 2) void attention_bf16_mfma(HstuDims hd, uint32_t layer, const uint16_t* __restrict__ q,
                                                               const float* __restrict__ pos,
                                                               const float* __restrict__ time, KvView kv,
                                                               const ReqDev* __restrict__ reqs,
                                                               const AttnItem* __restrict__ items,
+                                                              const AttnWork* __restrict__ work,
                                                               float* __restrict__ partials,
                                                               const int32_t* __restrict__ page_tables,
                                                               const long long* __restrict__ ts,
@@ -532,8 +534,10 @@ __global__ __launch_bounds__(256, NQB == 1 ? 3 : 2) void attention_bf16_mfma(Hst
   constexpr uint32_t kPosWin = kQ + 64;  // distances a tile can need (kQ + 63), padded
   __shared__ __attribute__((aligned(16))) AttnShared sm;
   const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, li = lane & 31;
-  const AttnItem item = items[blockIdx.x / hd.H];
-  const uint32_t r = item.req, qt = item.qt, h = blockIdx.x % hd.H;
+  const AttnWork wk = work[blockIdx.x];
+  if (wk.item == kNoWork) return;  // padding of a die's list
+  const AttnItem item = items[wk.item];
+  const uint32_t r = item.req, qt = item.qt, h = wk.head;
   const ReqDev rq = reqs[r];
   const uint32_t P = rq.prefix_len, T = rq.new_len, S = P + T;
   const uint32_t q0 = qt * kQ;  // first query (index among the new tokens) of the block
@@ -605,7 +609,6 @@ __global__ __launch_bounds__(256, NQB == 1 ? 3 : 2) void attention_bf16_mfma(Hst
     }
   }
   __syncthreads();
-  const uint32_t krow = (li & 0x13) | ((li & 8) >> 1) | ((li & 4) << 1);  // K row this lane feeds as MFMA row li
 
   // registers that carry the next tile from global memory to LDS
   uint4 kreg[2], vreg[2];
@@ -694,7 +697,9 @@ __global__ __launch_bounds__(256, NQB == 1 ? 3 : 2) void attention_bf16_mfma(Hst
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
       const uint32_t c = tid + 256 * it, row = c >> 3, part = c & 7;
-      *reinterpret_cast<uint4*>(&t.Ks[row][part * 8]) = kreg[it];
+      // key row r is stored at row perm(r) (bits 2 and 3 swapped): the first product then reads
+      // consecutive LDS rows, which the row padding keeps free of bank conflicts
+      *reinterpret_cast<uint4*>(&t.Ks[(row & 0x33) | ((row & 8) >> 1) | ((row & 4) << 1)][part * 8]) = kreg[it];
       *reinterpret_cast<uint4*>(&t.Vs[row][part * 8]) = vreg[it];
       if (c < kPosWin) {
 #pragma unroll
@@ -740,7 +745,7 @@ __global__ __launch_bounds__(256, NQB == 1 ? 3 : 2) void attention_bf16_mfma(Hst
       // operands are read from LDS right where they are consumed: holding all of them across
       // the epilogue would push the kernel past 256 registers
       auto k_frag = [&](int sb, int st) {
-        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&tl.Ks[32 * sb + krow][16 * st + 8 * g]));
+        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&tl.Ks[32 * sb + li][16 * st + 8 * g]));
       };
       auto v_frag = [&](int sb, int s2, int db) {
         return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&tl.Vs[32 * db + li][32 * sb + 16 * s2 + 8 * g]));
@@ -1037,14 +1042,10 @@ hipError_t launch_attention(const HstuDims& hd, uint32_t layer, const void* q, c
                             void* o, hipStream_t stream) {
   if (sl.N == 0) return hipSuccess;
   if (hd.elem == 1) {
-    if (sl.q_block == 128)
-      hipLaunchKernelGGL(attention_bf16_mfma<1>, dim3(sl.n_items * hd.H), dim3(256), 0, stream, hd, layer,
-                         static_cast<const uint16_t*>(q), pos, time, kv, sl.reqs, sl.items, sl.partials, page_tables,
-                         reinterpret_cast<const long long*>(ts), static_cast<uint16_t*>(o));
-    else
-      hipLaunchKernelGGL(attention_bf16_mfma<2>, dim3(sl.n_items * hd.H), dim3(256), 0, stream, hd, layer,
-                         static_cast<const uint16_t*>(q), pos, time, kv, sl.reqs, sl.items, sl.partials, page_tables,
-                         reinterpret_cast<const long long*>(ts), static_cast<uint16_t*>(o));
+    if (sl.q_block != 128) return hipErrorInvalidValue;  // the work items are cut for 128-query blocks
+    hipLaunchKernelGGL(attention_bf16_mfma<1>, dim3(sl.n_work), dim3(256), 0, stream, hd, layer,
+                       static_cast<const uint16_t*>(q), pos, time, kv, sl.reqs, sl.items, sl.work, sl.partials, page_tables,
+                       reinterpret_cast<const long long*>(ts), static_cast<uint16_t*>(o));
   } else {
     const uint32_t items = sl.N * hd.H;
     hipLaunchKernelGGL(attention_f32, dim3((items + 3) / 4), dim3(256), 0, stream, hd, layer,

@@ -93,9 +93,9 @@ struct KvView {
 };
 
 constexpr uint32_t kAttnQueries = 256;
-constexpr uint32_t kAttnMaxItemPages = 1024;  // page-table entries one attention item may span  // queries per attention work item (bf16 path)
+constexpr uint32_t kAttnMaxItemPages = 1024;  // page-table entries one attention item may span
 
-// One attention work item: q_block (128 or 256) queries of one request against the key tiles [kt_begin, kt_end)
+// One attention work item: q_block (128) queries of one request against the key tiles [kt_begin, kt_end)
 // (64 keys each).  A query tile whose key range was cut into several items accumulates
 // through fp32 partial slots (slot .. slot + chunks - 1) that a reduction pass adds up in
 // order; an item that covers its whole key range writes the output directly (slot = kDirect).
@@ -107,6 +107,17 @@ struct AttnGroup {
 };
 constexpr uint32_t kDirect = 0xFFFFFFFFu;
 
+// What one attention workgroup does: an item for one head.  Workgroup ids go round-robin over
+// the chip's kXcds dies, each with an L2 of its own, so entry i of the work list runs on die
+// i % kXcds: the host lays the list out so that the items of all query tiles that read the
+// same keys of the same head sit on one die, next to each other, and share those keys through
+// its L2 instead of each fetching them from memory.  Entries with item = kNoWork pad the list.
+struct AttnWork {
+  uint32_t item, head;
+};
+constexpr uint32_t kXcds = 8;
+constexpr uint32_t kNoWork = 0xFFFFFFFFu;
+
 // Up to 128 consecutive new-token rows of one request (projection GEMM tile)
 struct RowTile {
   uint32_t row0, rows, req, pad;
@@ -116,13 +127,15 @@ struct RowTile {
 struct StepLists {
   const ReqDev* reqs;        // [B]
   const uint32_t* row_req;   // [N] request of each new-token row
-  const AttnItem* items;     // largest first
+  const AttnItem* items;     // grouped by (request, key chunk)
+  const AttnWork* work;      // [n_work] workgroup -> (item, head), die-interleaved
+  uint32_t n_work;
   const AttnGroup* groups;   // query tiles that were split
   const RowTile* row_tiles;  // projection tiles, none crosses a request
   uint32_t n_row_tiles;
   float* partials;           // [slot][head][q_block][64]
   uint32_t n_items, n_groups;
-  uint32_t q_block;          // queries per item: 128 or 256
+  uint32_t q_block;          // queries per item
   uint32_t B, N;
 };
 

@@ -493,8 +493,8 @@ struct StepCtx {
   uint64_t esize;
 };
 
-// Validate the requests, build the row->request map and the attention work list (largest
-// amount of key tiles first), ship them to the device on `stream`.
+// Validate the requests, build the row->request map and the attention work lists, ship them
+// to the device on `stream`.
 int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, uint32_t B, uint64_t n_page_entries,
                      hipStream_t stream, StepCtx* ctx) {
   const racer_hstu_cfg& c = m->cfg;
@@ -515,41 +515,80 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
 
   // Attention work items.  The score matrix of a request is a staircase: late query tiles see
   // many more key tiles than early ones, and one long request would otherwise set the
-  // kernel's duration.  Key ranges are therefore cut into chunks of at most `chunk` tiles,
-  // sized so that about two items per resident block slot exist, and launched largest first.
+  // kernel's duration.  Key ranges are therefore cut at multiples of `chunk` tiles (sized so
+  // that about two items per resident block slot exist; a short tail joins the chunk before
+  // it), which also makes the items of different query tiles with the same chunk index read
+  // exactly the same keys.
   const uint32_t q_block = 128;
-  struct QTile { uint32_t req, qt, n_kt; };
+  struct QTile { uint32_t req, qt, n_kt, n_ch, slot0; };
   std::vector<QTile> qtiles;
   uint64_t visits = 0;
   for (uint32_t r = 0; r < B; ++r) {
     const uint32_t T = reqs[r].new_len;
     for (uint32_t qt = 0; qt * q_block < T; ++qt) {
       const uint64_t last = static_cast<uint64_t>(reqs[r].prefix_len) + std::min<uint64_t>(qt * q_block + q_block - 1, T - 1);
-      qtiles.push_back({r, qt, static_cast<uint32_t>(last / 64 + 1)});
+      qtiles.push_back({r, qt, static_cast<uint32_t>(last / 64 + 1), 0, 0});
       visits += last / 64 + 1;
     }
   }
-  const uint64_t block_slots = q_block == 128 ? 1024 : 512;  // 256 CUs x resident blocks
+  const uint64_t block_slots = 1024;  // about 256 CUs x resident blocks
   uint32_t chunk = static_cast<uint32_t>(std::max<uint64_t>(8, (visits * c.H + 2 * block_slots - 1) / (2 * block_slots)));
-  // an item's slice of the page table must fit the kernel's LDS copy
-  const uint32_t chunk_cap = static_cast<uint32_t>((static_cast<uint64_t>(racer::kAttnMaxItemPages) - 2) * c.page_tokens / 64);
+  // an item's slice of the page table (a chunk and a quarter at most) must fit the kernel's LDS copy
+  const uint32_t chunk_cap = static_cast<uint32_t>((static_cast<uint64_t>(racer::kAttnMaxItemPages) - 2) * c.page_tokens / 64 * 4 / 5);
   chunk = std::min(chunk, std::max<uint32_t>(1, chunk_cap));
-  std::vector<racer::AttnItem> items;
   std::vector<racer::AttnGroup> groups;
   uint32_t n_slots = 0;
-  for (const QTile& t : qtiles) {
-    const uint32_t chunks = (t.n_kt + chunk - 1) / chunk;
-    const uint32_t per = (t.n_kt + chunks - 1) / chunks;
-    if (chunks > 1) groups.push_back({t.req, t.qt, n_slots, chunks});
-    for (uint32_t k = 0; k < chunks; ++k) {
-      const uint32_t b = k * per, e = std::min(t.n_kt, b + per);
-      items.push_back({t.req, t.qt, b, e, chunks > 1 ? n_slots + k : racer::kDirect, 0});
+  for (QTile& t : qtiles) {
+    t.n_ch = t.n_kt / chunk;
+    if (t.n_ch == 0 || t.n_kt % chunk > chunk / 4) ++t.n_ch;
+    if (t.n_ch > 1) {
+      t.slot0 = n_slots;
+      groups.push_back({t.req, t.qt, n_slots, t.n_ch});
+      n_slots += t.n_ch;
     }
-    if (chunks > 1) n_slots += chunks;
   }
-  std::stable_sort(items.begin(), items.end(), [](const racer::AttnItem& a, const racer::AttnItem& b) {
-    return a.kt_end - a.kt_begin > b.kt_end - b.kt_begin;
-  });
+  // units: the items of one request with the same chunk index, for one head
+  struct Unit { uint32_t item0, n_items; uint64_t weight; };
+  std::vector<racer::AttnItem> items;
+  std::vector<Unit> units;
+  for (size_t q0 = 0; q0 < qtiles.size();) {
+    size_t q1 = q0;
+    uint32_t max_ch = 0;
+    while (q1 < qtiles.size() && qtiles[q1].req == qtiles[q0].req) max_ch = std::max(max_ch, qtiles[q1++].n_ch);
+    for (uint32_t k = 0; k < max_ch; ++k) {
+      Unit u{static_cast<uint32_t>(items.size()), 0, 0};
+      for (size_t q = q0; q < q1; ++q) {
+        const QTile& t = qtiles[q];
+        if (k >= t.n_ch) continue;
+        const uint32_t b = k * chunk, e = k + 1 == t.n_ch ? t.n_kt : b + chunk;
+        items.push_back({t.req, t.qt, b, e, t.n_ch > 1 ? t.slot0 + k : racer::kDirect, 0});
+        u.weight += e - b;
+      }
+      u.n_items = static_cast<uint32_t>(items.size()) - u.item0;
+      units.push_back(u);
+    }
+    q0 = q1;
+  }
+  // heaviest unit first onto the least loaded die; a die's list keeps that order, so its last
+  // workgroups are the short ones
+  std::vector<uint32_t> order(units.size());
+  for (uint32_t i = 0; i < order.size(); ++i) order[i] = i;
+  std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return units[a].weight > units[b].weight; });
+  std::vector<racer::AttnWork> die_list[racer::kXcds];
+  uint64_t die_load[racer::kXcds] = {};
+  for (uint32_t ui : order)
+    for (uint32_t h = 0; h < c.H; ++h) {
+      uint32_t best = 0;
+      for (uint32_t x = 1; x < racer::kXcds; ++x)
+        if (die_load[x] < die_load[best]) best = x;
+      die_load[best] += units[ui].weight;
+      for (uint32_t i = 0; i < units[ui].n_items; ++i) die_list[best].push_back({units[ui].item0 + i, h});
+    }
+  size_t die_len = 0;
+  for (uint32_t x = 0; x < racer::kXcds; ++x) die_len = std::max(die_len, die_list[x].size());
+  std::vector<racer::AttnWork> work(die_len * racer::kXcds, racer::AttnWork{racer::kNoWork, 0});
+  for (uint32_t x = 0; x < racer::kXcds; ++x)
+    for (size_t i = 0; i < die_list[x].size(); ++i) work[i * racer::kXcds + x] = die_list[x][i];
   const uint64_t partial_bytes = static_cast<uint64_t>(n_slots) * c.H * q_block * 64 * sizeof(float);
   if (partial_bytes > p->hp_cap) {
     HIP_TRY(hipStreamSynchronize(p->last_stream));
@@ -570,10 +609,12 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
     for (uint32_t t0 = 0; t0 < reqs[r].new_len; t0 += 128)
       row_tiles.push_back({static_cast<uint32_t>(reqs[r].x_off) + t0, std::min<uint32_t>(128, reqs[r].new_len - t0), r, 0});
   const uint64_t bytes_row_tiles = sizeof(racer::RowTile) * std::max<size_t>(row_tiles.size(), 1);
+  const uint64_t bytes_work = sizeof(racer::AttnWork) * std::max<size_t>(work.size(), 1);
   const uint64_t off_rows = (bytes_reqs + 255) & ~255ull, off_items = (off_rows + bytes_rows + 255) & ~255ull;
   const uint64_t off_groups = (off_items + bytes_items + 255) & ~255ull;
   const uint64_t off_row_tiles = (off_groups + bytes_groups + 255) & ~255ull;
-  const uint64_t total = off_row_tiles + bytes_row_tiles;
+  const uint64_t off_work = (off_row_tiles + bytes_row_tiles + 255) & ~255ull;
+  const uint64_t total = off_work + bytes_work;
   if (total > p->hl_cap) {
     HIP_TRY(hipStreamSynchronize(p->last_stream));
     if (p->hl_dev) HIP_TRY(hipFree(p->hl_dev));
@@ -596,6 +637,7 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   if (!items.empty()) std::memcpy(hbuf + off_items, items.data(), sizeof(racer::AttnItem) * items.size());
   if (!groups.empty()) std::memcpy(hbuf + off_groups, groups.data(), sizeof(racer::AttnGroup) * groups.size());
   if (!row_tiles.empty()) std::memcpy(hbuf + off_row_tiles, row_tiles.data(), sizeof(racer::RowTile) * row_tiles.size());
+  if (!work.empty()) std::memcpy(hbuf + off_work, work.data(), sizeof(racer::AttnWork) * work.size());
   HIP_TRY(hipMemcpyAsync(p->hl_dev, hbuf, total, hipMemcpyHostToDevice, stream));
   if ((rc = p->hstage.mark(which, stream))) return rc;
 
@@ -611,6 +653,8 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   ctx->sl.groups = reinterpret_cast<const racer::AttnGroup*>(p->hl_dev + off_groups);
   ctx->sl.partials = reinterpret_cast<float*>(p->hp_dev);
   ctx->sl.n_items = static_cast<uint32_t>(items.size());
+  ctx->sl.work = reinterpret_cast<const racer::AttnWork*>(p->hl_dev + off_work);
+  ctx->sl.n_work = static_cast<uint32_t>(work.size());
   ctx->sl.n_groups = static_cast<uint32_t>(groups.size());
   ctx->sl.q_block = q_block;
   ctx->sl.row_tiles = reinterpret_cast<const racer::RowTile*>(p->hl_dev + off_row_tiles);
