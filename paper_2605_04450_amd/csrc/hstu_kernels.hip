@@ -386,6 +386,288 @@ __global__ __launch_bounds__(256) void gemm_front_bf16(HstuDims hd, uint32_t lay
 }
 
 // fp32 GEMM for the small configuration: one thread per output, W is [K][Nout]
+// ---------------------------------------------------------------------------------------
+// Fused layer halves for bf16 models with d = KD <= 256 (one kernel each, no normalised copy
+// of the activations in memory):
+//   FRONT: [U|V|Q|K] = SiLU(LN1(X) W1 + b1), U and Q*log2(e) to row-major buffers, K and V into
+//          the pages;
+//   BACK:  Y = X + (LN2(O) * U) W2 + b2.
+// A wavefront owns 32 token rows.  Their activations are loaded once, normalised in registers
+// (a row is split over the two lanes (g = 0, 1) that share the token: two cross-lane sums) and
+// kept as the token-side MFMA operand for the whole sweep over the output columns, KD/16
+// fragments of 8 elements.  The weights (stored transposed, [out][KD]) pass through LDS in
+// tiles of 32 output columns, double buffered with one barrier per tile; chunk c of tile row R
+// sits at chunk position c ^ (R & 7) so that the operand reads of eight neighbouring lanes
+// (eight rows, same c) hit different banks.  The product is taken as (W tile) x (X^T), so a
+// lane ends up with one token and 16 output features (four runs of four), which gives 8-byte
+// stores for row-major outputs and K, and lane-coalesced 2-byte stores for V^T.
+// WPB = wavefronts per block (a block covers 32 * WPB rows of a row tile of up to 128 rows).
+// ---------------------------------------------------------------------------------------
+struct LayerHalfArgs {
+  HstuDims hd;
+  uint32_t layer;
+  const uint16_t* a_in;    // FRONT: X   BACK: O       [N][KD]
+  const uint16_t* gate;    // BACK: U
+  const float* ln_g;
+  const float* ln_b;
+  const uint16_t* wt;      // [n_out][KD] of this layer
+  const float* bias;       // [n_out]
+  uint16_t* u;             // FRONT outputs
+  uint16_t* q;
+  KvView kv;
+  const ReqDev* reqs;
+  const int32_t* page_tables;
+  const uint16_t* resid;   // BACK: X
+  uint16_t* y;             // BACK output
+  const RowTile* row_tiles;
+  uint32_t col_blocks_per_split;  // 32-column tiles one block sweeps
+};
+
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
+  typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+  typedef float v2f __attribute__((ext_vector_type(2)));
+  const v2f v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, v2bf));
+}
+__device__ __forceinline__ void unpack8(const uint4& a, float v[8]) {
+  const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    v[2 * k] = __uint_as_float(w[k] << 16);
+    v[2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
+  }
+}
+
+// Tells the compiler nothing about the value it returns: the unpacked fp32 copy of a row that an
+// earlier pass over the registers made cannot be kept alive for a later pass (it would double
+// the registers the row takes).
+__device__ __forceinline__ void forget(uint4& a) { asm volatile("" : "+v"(a.x), "+v"(a.y), "+v"(a.z), "+v"(a.w)); }
+
+template <int KD, bool FRONT, int WPB>
+__global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgpu_waves_per_eu(3, 3))) void layer_half_fused(LayerHalfArgs a) {
+  constexpr int kSt = KD / 16;                 // MFMA steps over the contraction
+  constexpr int kTileChunks = 32 * KD / 8;     // 16-byte chunks of a weight tile
+  constexpr int kPerThread = kTileChunks / (64 * WPB);
+  constexpr int kRowChunks = KD / 8;
+  static_assert(kTileChunks % (64 * WPB) == 0, "weight tile must split evenly over the block");
+  __shared__ __attribute__((aligned(16))) uint16_t wtile[2][32 * KD];
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, li = lane & 31;
+  const RowTile rt = a.row_tiles[blockIdx.x / (4 / WPB)];
+  const uint32_t sub = blockIdx.x % (4 / WPB);
+  if (32 * WPB * sub >= rt.rows) return;  // this part of the row tile is empty
+  const uint32_t rloc = 32 * (WPB * sub + wave) + li;  // row inside the tile
+  const bool row_ok = rloc < rt.rows;
+  const uint64_t row = rt.row0 + (row_ok ? rloc : 0);
+  const HstuDims& hd = a.hd;
+
+  // ---- activations: load, normalise, keep as MFMA operand ----------------------------------
+  __shared__ __attribute__((aligned(16))) float lnp[2][KD];  // LayerNorm scale and shift
+  for (uint32_t i = tid; i < KD; i += 64 * WPB) {
+    lnp[0][i] = a.ln_g[i];
+    lnp[1][i] = a.ln_b[i];
+  }
+  uint4 xr[kSt];  // this lane's half of its token's row: raw, then normalised (and gated) bf16
+#pragma unroll
+  for (int st = 0; st < kSt; ++st) {
+    xr[st] = make_uint4(0, 0, 0, 0);
+    if (row_ok) xr[st] = *reinterpret_cast<const uint4*>(a.a_in + row * KD + 16 * st + 8 * g);
+  }
+  {
+    uint4 gr[FRONT ? 1 : kSt];  // BACK: the gate row
+    if (!FRONT) {
+#pragma unroll
+      for (int st = 0; st < kSt; ++st) {
+        gr[st] = make_uint4(0, 0, 0, 0);
+        if (row_ok) gr[st] = *reinterpret_cast<const uint4*>(a.gate + row * KD + 16 * st + 8 * g);
+      }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int st = 0; st < kSt; ++st) {
+      float v[8];
+      unpack8(xr[st], v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s += v[e];
+    }
+    s += __shfl_xor(s, 32, 64);
+    const float mean = s / KD;
+    float qq = 0.0f;
+#pragma unroll
+    for (int st = 0; st < kSt; ++st) forget(xr[st]);
+#pragma unroll
+    for (int st = 0; st < kSt; ++st) {
+      float v[8];
+      unpack8(xr[st], v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qq += (v[e] - mean) * (v[e] - mean);
+    }
+    qq += __shfl_xor(qq, 32, 64);
+    const float rstd = 1.0f / sqrtf(qq / KD + hd.eps);
+    __syncthreads();  // lnp is visible
+#pragma unroll
+    for (int st = 0; st < kSt; ++st) forget(xr[st]);
+#pragma unroll
+    for (int st = 0; st < kSt; ++st) {
+      float v[8], gg[8], bb[8];
+      unpack8(xr[st], v);
+      load8(&lnp[0][16 * st + 8 * g], gg);
+      load8(&lnp[1][16 * st + 8 * g], bb);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = (v[e] - mean) * rstd * gg[e] + bb[e];
+      if (!FRONT) {
+        float uv[8];
+        unpack8(gr[st], uv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= uv[e];
+      }
+      xr[st] = make_uint4(pack2_bf16(v[0], v[1]), pack2_bf16(v[2], v[3]), pack2_bf16(v[4], v[5]), pack2_bf16(v[6], v[7]));
+      // the result is pinned down here and memory operations may not pass: the LDS reads of later
+      // steps stay behind this step's arithmetic instead of piling up in registers
+      forget(xr[st]);
+      asm volatile("" ::: "memory");
+
+    }
+  }
+
+  // ---- where this lane's token goes ---------------------------------------------------------
+  const uint8_t* page_ptr = nullptr;  // FRONT: start of the token's page (nullptr: bad page id)
+  uint32_t tok = 0;
+  if (FRONT) {
+    const ReqDev rq = a.reqs[rt.req];
+    const uint32_t pos = rq.prefix_len + static_cast<uint32_t>(row - rq.x_off);
+    uint32_t pi;
+    split_token(hd, pos, &pi, &tok);
+    if (row_ok) {
+      const int32_t page = a.page_tables[rq.page_table_off + pi];
+      if (page < 0 || static_cast<uint32_t>(page) >= a.kv.n_pages) {
+        if (blockIdx.y == 0 && g == 0) atomicAdd(&a.kv.counters[ctr_index(kCtrBadPages)], 1ull);
+      } else {
+        page_ptr = a.kv.base + static_cast<uint64_t>(page) * a.kv.page_size;
+      }
+    }
+  }
+
+  // ---- sweep over the output columns ----------------------------------------------------------
+  // weight tiles travel global -> registers -> LDS, two tiles ahead of their use (two register sets;
+  // named members and spelled-out steps, so that they are registers whatever the optimiser's unrolling order)
+  struct WSet { uint4 c0, c1, c2, c3; };
+  static_assert(kPerThread == 2 || kPerThread == 4, "a thread stages two or four chunks of a weight tile");
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  WSet wregA{zero4, zero4, zero4, zero4}, wregB{zero4, zero4, zero4, zero4};
+  auto fetch_w = [&](WSet& wr, uint32_t cb) {
+    const uint4* src = reinterpret_cast<const uint4*>(a.wt + static_cast<uint64_t>(cb) * 32 * KD) + tid;
+    wr.c0 = src[0];
+    wr.c1 = src[64 * WPB];
+    if (kPerThread == 4) {
+      wr.c2 = src[2 * 64 * WPB];
+      wr.c3 = src[3 * 64 * WPB];
+    }
+  };
+  auto put_w = [&](const uint4& v, uint32_t it, uint16_t* dst) {
+    const uint32_t c = tid + 64 * WPB * it, R = c / kRowChunks, ch = c % kRowChunks;
+    *reinterpret_cast<uint4*>(dst + R * KD + 8 * (ch ^ (R & 7))) = v;
+  };
+  auto commit_w = [&](const WSet& wr, uint16_t* dst) {
+    put_w(wr.c0, 0, dst);
+    put_w(wr.c1, 1, dst);
+    if (kPerThread == 4) {
+      put_w(wr.c2, 2, dst);
+      put_w(wr.c3, 3, dst);
+    }
+  };
+  uint32_t swz[4];  // element offset of chunk 2 j + g (j < 4) inside this lane's tile row
+#pragma unroll
+  for (uint32_t j = 0; j < 4; ++j) swz[j] = li * KD + 8 * ((2 * j + g) ^ (li & 7));
+
+  // one 32-column tile: product, epilogue, stores
+  auto compute = [&](const uint16_t* wb, uint32_t cb) {
+    const uint32_t n0 = cb * 32;
+    // acc[e]: feature n0 + 8*(e/4) + 4*g + e%4 of this lane's token; the bias is the starting value
+    f32x16 acc;
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      const float4 b = *reinterpret_cast<const float4*>(a.bias + n0 + 8 * r4 + 4 * g);
+      acc[4 * r4] = b.x; acc[4 * r4 + 1] = b.y; acc[4 * r4 + 2] = b.z; acc[4 * r4 + 3] = b.w;
+    }
+#pragma unroll
+    for (int st = 0; st < kSt; ++st) {
+      const bf16x8 wf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(wb + swz[st & 3] + 64 * (st >> 2)));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, __builtin_bit_cast(bf16x8, xr[st]), acc, 0, 0, 0);
+    }
+    if (!row_ok) return;
+    if (FRONT) {
+      const uint32_t which = n0 / KD, c0 = n0 % KD;  // 0: U, 1: V, 2: Q, 3: K
+      float z[16];
+#pragma unroll
+#ifdef EXP_FNOSILU
+      for (int e = 0; e < 16; ++e) z[e] = acc[e];
+#else
+      for (int e = 0; e < 16; ++e) z[e] = silu(acc[e]);
+#endif
+#ifdef EXP_FNOSTORE
+      float zs = 0.0f;
+      for (int e = 0; e < 16; ++e) zs += z[e];
+      if (zs != 12345.678f) return;
+#endif
+      if (which == 0 || which == 2) {
+        uint16_t* dst = (which == 0 ? a.u : a.q) + row * KD + c0 + 4 * g;
+        const float sc = which == 2 ? 1.4426950408889634f : 1.0f;  // the attention kernel wants q * log2(e)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4)
+          *reinterpret_cast<uint2*>(dst + 8 * r4) = make_uint2(pack2_bf16(z[4 * r4] * sc, z[4 * r4 + 1] * sc),
+                                                                pack2_bf16(z[4 * r4 + 2] * sc, z[4 * r4 + 3] * sc));
+      } else if (page_ptr) {
+        const uint32_t head = c0 / 64, cc = c0 % 64 + 4 * g;
+        if (which == 3) {  // K block [token][64]
+          uint16_t* dst = reinterpret_cast<uint16_t*>(const_cast<uint8_t*>(page_ptr) + kv_block_offset(hd, a.layer, 0, head, 2)) +
+                          static_cast<uint64_t>(tok) * 64 + cc;
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4)
+            *reinterpret_cast<uint2*>(dst + 8 * r4) = make_uint2(pack2_bf16(z[4 * r4], z[4 * r4 + 1]), pack2_bf16(z[4 * r4 + 2], z[4 * r4 + 3]));
+        } else {  // V block [64][page_tokens]: the 32 lanes of a half-wave write 32 consecutive tokens of one feature
+          uint16_t* dst = reinterpret_cast<uint16_t*>(const_cast<uint8_t*>(page_ptr) + kv_block_offset(hd, a.layer, 1, head, 2)) + tok;
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            dst[static_cast<uint64_t>(cc + 8 * (e / 4) + e % 4) * hd.pt] = static_cast<uint16_t>(pack2_bf16(z[e], 0.0f));
+        }
+      }
+    } else {
+      const uint16_t* xr = a.resid + row * KD + n0 + 4 * g;
+      uint16_t* dst = a.y + row * KD + n0 + 4 * g;
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const uint2 xv = *reinterpret_cast<const uint2*>(xr + 8 * r4);
+        const float x0 = __uint_as_float(xv.x << 16), x1 = __uint_as_float(xv.x & 0xFFFF0000u);
+        const float x2 = __uint_as_float(xv.y << 16), x3 = __uint_as_float(xv.y & 0xFFFF0000u);
+        *reinterpret_cast<uint2*>(dst + 8 * r4) = make_uint2(pack2_bf16(x0 + acc[4 * r4], x1 + acc[4 * r4 + 1]),
+                                                              pack2_bf16(x2 + acc[4 * r4 + 2], x3 + acc[4 * r4 + 3]));
+      }
+    }
+  };
+
+  const uint32_t cb0 = blockIdx.y * a.col_blocks_per_split, n_cb = a.col_blocks_per_split;
+  fetch_w(wregA, cb0);
+  if (n_cb > 1) fetch_w(wregB, cb0 + 1);
+  commit_w(wregA, wtile[0]);
+  if (n_cb > 2) fetch_w(wregA, cb0 + 2);
+  for (uint32_t k = 0; k < n_cb; k += 2) {
+    // tile k is visible, and every wave is done with tile k-1, whose buffer takes tile k+1
+    __syncthreads();
+    if (k + 1 < n_cb) {
+      commit_w(wregB, wtile[1]);
+      if (k + 3 < n_cb) fetch_w(wregB, cb0 + k + 3);
+    }
+    compute(wtile[0], cb0 + k);
+    if (k + 1 >= n_cb) break;
+    __syncthreads();
+    if (k + 2 < n_cb) {
+      commit_w(wregA, wtile[0]);
+      if (k + 4 < n_cb) fetch_w(wregA, cb0 + k + 4);
+    }
+    compute(wtile[1], cb0 + k + 1);
+  }
+}
+
 template <typename Epi>
 __global__ __launch_bounds__(256) void gemm_f32_simple(const float* __restrict__ A, const float* __restrict__ W,
                                                        uint32_t M, uint32_t K, uint32_t Nout, Epi epi) {
@@ -1001,6 +1283,59 @@ hipError_t launch_layernorm(const HstuDims& hd, const void* x, const float* g, c
   if (N == 0) return hipSuccess;
   if (hd.elem == 1) layernorm_dispatch<bf16_t>(hd, x, g, b, gate, y, N, stream);
   else layernorm_dispatch<float>(hd, x, g, b, gate, y, N, stream);
+  return hipGetLastError();
+}
+
+bool layer_halves_fused(const HstuDims& hd) { return hd.elem == 1 && (hd.d == 128 || hd.d == 256); }
+
+hipError_t launch_layer_front_fused(const HstuDims& hd, uint32_t layer, const void* x, const float* ln_g,
+                                    const float* ln_b, const void* w1t, const float* b1, void* u, void* q,
+                                    const KvView& kv, const StepLists& sl, const int32_t* page_tables,
+                                    hipStream_t stream) {
+  if (sl.N == 0) return hipSuccess;
+  if (!layer_halves_fused(hd)) return hipErrorInvalidValue;
+  LayerHalfArgs a{};
+  a.hd = hd;
+  a.layer = layer;
+  a.a_in = static_cast<const uint16_t*>(x);
+  a.ln_g = ln_g;
+  a.ln_b = ln_b;
+  a.wt = static_cast<const uint16_t*>(w1t);
+  a.bias = b1;
+  a.u = static_cast<uint16_t*>(u);
+  a.q = static_cast<uint16_t*>(q);
+  a.kv = kv;
+  a.reqs = sl.reqs;
+  a.page_tables = page_tables;
+  a.row_tiles = sl.row_tiles;
+  constexpr uint32_t kSplit = 2;  // column halves: U|V and Q|K
+  a.col_blocks_per_split = 4 * hd.d / 32 / kSplit;
+  const dim3 grid(sl.n_row_tiles, kSplit), block(256);
+  if (hd.d == 256) hipLaunchKernelGGL((layer_half_fused<256, true, 4>), grid, block, 0, stream, a);
+  else hipLaunchKernelGGL((layer_half_fused<128, true, 4>), grid, block, 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_layer_back_fused(const HstuDims& hd, const void* o, const void* u, const float* ln_g,
+                                   const float* ln_b, const void* w2t, const float* b2, const void* x, void* y,
+                                   const StepLists& sl, hipStream_t stream) {
+  if (sl.N == 0) return hipSuccess;
+  if (!layer_halves_fused(hd)) return hipErrorInvalidValue;
+  LayerHalfArgs a{};
+  a.hd = hd;
+  a.a_in = static_cast<const uint16_t*>(o);
+  a.gate = static_cast<const uint16_t*>(u);
+  a.ln_g = ln_g;
+  a.ln_b = ln_b;
+  a.wt = static_cast<const uint16_t*>(w2t);
+  a.bias = b2;
+  a.resid = static_cast<const uint16_t*>(x);
+  a.y = static_cast<uint16_t*>(y);
+  a.row_tiles = sl.row_tiles;
+  a.col_blocks_per_split = hd.d / 32;
+  const dim3 grid(sl.n_row_tiles, 1), block(256);
+  if (hd.d == 256) hipLaunchKernelGGL((layer_half_fused<256, false, 4>), grid, block, 0, stream, a);
+  else hipLaunchKernelGGL((layer_half_fused<128, false, 4>), grid, block, 0, stream, a);
   return hipGetLastError();
 }
 

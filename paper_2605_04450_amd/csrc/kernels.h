@@ -147,6 +147,16 @@ hipError_t launch_gemm_front(const HstuDims& hd, uint32_t layer, const void* xn,
                              const int32_t* page_tables, hipStream_t stream);
 hipError_t launch_gemm_back(const HstuDims& hd, const void* g, const void* w2t, const float* b2,
                             const void* x, void* y, uint32_t N, hipStream_t stream);
+// bf16 models with d = 128 or 256: LayerNorm, projection and epilogue of a layer half in one kernel
+// (front: X -> U, Q*log2(e), K/V pages; back: O, U, X -> Y); weights transposed as for the GEMMs
+bool layer_halves_fused(const HstuDims& hd);
+hipError_t launch_layer_front_fused(const HstuDims& hd, uint32_t layer, const void* x, const float* ln_g,
+                                    const float* ln_b, const void* w1t, const float* b1, void* u, void* q,
+                                    const KvView& kv, const StepLists& sl, const int32_t* page_tables,
+                                    hipStream_t stream);
+hipError_t launch_layer_back_fused(const HstuDims& hd, const void* o, const void* u, const float* ln_g,
+                                   const float* ln_b, const void* w2t, const float* b2, const void* x, void* y,
+                                   const StepLists& sl, hipStream_t stream);
 hipError_t launch_attention(const HstuDims& hd, uint32_t layer, const void* q, const float* pos,
                             const float* time, const KvView& kv, const StepLists& sl,
                             const int32_t* page_tables, const int64_t* ts, void* o, hipStream_t stream);

@@ -717,11 +717,15 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
     const float* b2 = static_cast<const float*>(m->w.b2) + l * d;
     const uint8_t* w1 = static_cast<const uint8_t*>(bf16 ? m->w1t : m->w.w1) + l * w1_layer;
     const uint8_t* w2 = static_cast<const uint8_t*>(bf16 ? m->w2t : m->w.w2) + l * w2_layer;
-    {
-      ProfScope t(p, RACER_PROF_LAYERNORM, stream);
-      HIP_TRY(racer::launch_layernorm(ctx.hd, x_cur, ln1_g, ln1_b, nullptr, xn, N, stream));
-    }
-    {
+    const bool fused = racer::layer_halves_fused(ctx.hd);
+    if (fused) {
+      ProfScope t(p, RACER_PROF_GEMM_FRONT, stream);
+      HIP_TRY(racer::launch_layer_front_fused(ctx.hd, l, x_cur, ln1_g, ln1_b, w1, b1, u, q, ctx.kv, ctx.sl, page_tables, stream));
+    } else {
+      {
+        ProfScope t(p, RACER_PROF_LAYERNORM, stream);
+        HIP_TRY(racer::launch_layernorm(ctx.hd, x_cur, ln1_g, ln1_b, nullptr, xn, N, stream));
+      }
       ProfScope t(p, RACER_PROF_GEMM_FRONT, stream);
       HIP_TRY(racer::launch_gemm_front(ctx.hd, l, xn, w1, b1, u, q, ctx.kv, ctx.sl, page_tables, stream));
     }
@@ -735,11 +739,14 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
       ProfScope t(p, RACER_PROF_ATTN_REDUCE, stream);
       HIP_TRY(racer::launch_attention_reduce(ctx.hd, ctx.sl, o, stream));
     }
-    {
-      ProfScope t(p, RACER_PROF_LAYERNORM, stream);
-      HIP_TRY(racer::launch_layernorm(ctx.hd, o, ln2_g, ln2_b, u, xn, N, stream));
-    }
-    {
+    if (fused) {
+      ProfScope t(p, RACER_PROF_GEMM_BACK, stream);
+      HIP_TRY(racer::launch_layer_back_fused(ctx.hd, o, u, ln2_g, ln2_b, w2, b2, x_cur, x_next, ctx.sl, stream));
+    } else {
+      {
+        ProfScope t(p, RACER_PROF_LAYERNORM, stream);
+        HIP_TRY(racer::launch_layernorm(ctx.hd, o, ln2_g, ln2_b, u, xn, N, stream));
+      }
       ProfScope t(p, RACER_PROF_GEMM_BACK, stream);
       HIP_TRY(racer::launch_gemm_back(ctx.hd, xn, w2, b2, x_cur, x_next, N, stream));
     }
