@@ -547,6 +547,32 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
     }
   }
 
+  // Row-major outputs leave through a wave-private LDS tile that turns "one token, four runs of four
+  // features per lane" into 16-byte pieces: lane l then stores features 8 (l % 4) .. + 8 of the tokens
+  // l / 4 and l / 4 + 16 of its wavefront, so four lanes cover 64 contiguous bytes of a row.
+  const bool wave_has_rows = 32 * (WPB * sub + wave) < rt.rows;
+  bool ok2[2];
+  uint64_t row2[2];
+  uint8_t* kdst2[2] = {nullptr, nullptr};  // FRONT: K row of the token inside its page, before the head offset
+#pragma unroll
+  for (int h2 = 0; h2 < 2; ++h2) {
+    const uint32_t rl = 32 * (WPB * sub + wave) + (lane >> 2) + 16 * h2;
+    ok2[h2] = rl < rt.rows;
+    row2[h2] = rt.row0 + (ok2[h2] ? rl : 0);
+    if (FRONT && ok2[h2]) {
+      const ReqDev rq = a.reqs[rt.req];
+      const uint32_t pos = rq.prefix_len + static_cast<uint32_t>(row2[h2] - rq.x_off);
+      uint32_t pi, tk;
+      split_token(hd, pos, &pi, &tk);
+      const int32_t page = a.page_tables[rq.page_table_off + pi];
+      if (page >= 0 && static_cast<uint32_t>(page) < a.kv.n_pages)
+        kdst2[h2] = a.kv.base + static_cast<uint64_t>(page) * a.kv.page_size + static_cast<uint64_t>(tk) * 128;
+    }
+  }
+  constexpr int kOutStride = FRONT ? 40 : 72;  // 16-bit units per token row of the tile: 32 bf16 or 32 fp32, padded
+  __shared__ __attribute__((aligned(16))) uint16_t otile[WPB][32 * kOutStride];
+  uint16_t* ot = otile[wave];
+
   // ---- sweep over the output columns ----------------------------------------------------------
   // weight tiles travel global -> registers -> LDS, two tiles ahead of their use (two register sets;
   // named members and spelled-out steps, so that they are registers whatever the optimiser's unrolling order)
@@ -582,8 +608,8 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
   // one 32-column tile: product, epilogue, stores
   auto compute = [&](const uint16_t* wb, uint32_t cb) {
     const uint32_t n0 = cb * 32;
-    // acc[e]: feature n0 + 8*(e/4) + 4*g + e%4 of this lane's token; the bias is the starting value
     f32x16 acc;
+    // acc[e]: feature n0 + 8*(e/4) + 4*g + e%4 of this lane's token; the bias is the starting value
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
       const float4 b = *reinterpret_cast<const float4*>(a.bias + n0 + 8 * r4 + 4 * g);
@@ -594,53 +620,54 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
       const bf16x8 wf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(wb + swz[st & 3] + 64 * (st >> 2)));
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, __builtin_bit_cast(bf16x8, xr[st]), acc, 0, 0, 0);
     }
-    if (!row_ok) return;
+    if (!wave_has_rows) return;
     if (FRONT) {
       const uint32_t which = n0 / KD, c0 = n0 % KD;  // 0: U, 1: V, 2: Q, 3: K
       float z[16];
 #pragma unroll
-#ifdef EXP_FNOSILU
-      for (int e = 0; e < 16; ++e) z[e] = acc[e];
-#else
-      for (int e = 0; e < 16; ++e) z[e] = silu(acc[e]);
-#endif
-#ifdef EXP_FNOSTORE
-      float zs = 0.0f;
-      for (int e = 0; e < 16; ++e) zs += z[e];
-      if (zs != 12345.678f) return;
-#endif
-      if (which == 0 || which == 2) {
-        uint16_t* dst = (which == 0 ? a.u : a.q) + row * KD + c0 + 4 * g;
-        const float sc = which == 2 ? 1.4426950408889634f : 1.0f;  // the attention kernel wants q * log2(e)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4)
-          *reinterpret_cast<uint2*>(dst + 8 * r4) = make_uint2(pack2_bf16(z[4 * r4] * sc, z[4 * r4 + 1] * sc),
-                                                                pack2_bf16(z[4 * r4 + 2] * sc, z[4 * r4 + 3] * sc));
-      } else if (page_ptr) {
-        const uint32_t head = c0 / 64, cc = c0 % 64 + 4 * g;
-        if (which == 3) {  // K block [token][64]
-          uint16_t* dst = reinterpret_cast<uint16_t*>(const_cast<uint8_t*>(page_ptr) + kv_block_offset(hd, a.layer, 0, head, 2)) +
-                          static_cast<uint64_t>(tok) * 64 + cc;
-#pragma unroll
-          for (int r4 = 0; r4 < 4; ++r4)
-            *reinterpret_cast<uint2*>(dst + 8 * r4) = make_uint2(pack2_bf16(z[4 * r4], z[4 * r4 + 1]), pack2_bf16(z[4 * r4 + 2], z[4 * r4 + 3]));
-        } else {  // V block [64][page_tokens]: the 32 lanes of a half-wave write 32 consecutive tokens of one feature
+      for (int e = 0; e < 16; ++e) z[e] = acc[e] * __builtin_amdgcn_rcpf(1.0f + __expf(-acc[e]));
+      if (which == 1) {
+        // V block [64][page_tokens]: the 32 lanes of a half-wave write 32 consecutive tokens of one feature
+        if (page_ptr) {
+          const uint32_t head = c0 / 64, cc = c0 % 64 + 4 * g;
           uint16_t* dst = reinterpret_cast<uint16_t*>(const_cast<uint8_t*>(page_ptr) + kv_block_offset(hd, a.layer, 1, head, 2)) + tok;
 #pragma unroll
           for (int e = 0; e < 16; ++e)
             dst[static_cast<uint64_t>(cc + 8 * (e / 4) + e % 4) * hd.pt] = static_cast<uint16_t>(pack2_bf16(z[e], 0.0f));
         }
+        return;
+      }
+      const float sc = which == 2 ? 1.4426950408889634f : 1.0f;  // the attention kernel wants q * log2(e)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4)
+        *reinterpret_cast<uint2*>(ot + li * kOutStride + 8 * r4 + 4 * g) =
+            make_uint2(pack2_bf16(z[4 * r4] * sc, z[4 * r4 + 1] * sc), pack2_bf16(z[4 * r4 + 2] * sc, z[4 * r4 + 3] * sc));
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2) {
+        const uint4 v = *reinterpret_cast<const uint4*>(ot + ((lane >> 2) + 16 * h2) * kOutStride + 8 * (lane & 3));
+        if (which == 3) {  // K block [token][64]
+          if (kdst2[h2])
+            *reinterpret_cast<uint4*>(kdst2[h2] + kv_block_offset(hd, a.layer, 0, c0 / 64, 2) + (c0 % 64 + 8 * (lane & 3)) * 2) = v;
+        } else if (ok2[h2]) {
+          *reinterpret_cast<uint4*>((which == 0 ? a.u : a.q) + row2[h2] * KD + c0 + 8 * (lane & 3)) = v;
+        }
       }
     } else {
-      const uint16_t* xr = a.resid + row * KD + n0 + 4 * g;
-      uint16_t* dst = a.y + row * KD + n0 + 4 * g;
+      float* otf = reinterpret_cast<float*>(ot);
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const uint2 xv = *reinterpret_cast<const uint2*>(xr + 8 * r4);
-        const float x0 = __uint_as_float(xv.x << 16), x1 = __uint_as_float(xv.x & 0xFFFF0000u);
-        const float x2 = __uint_as_float(xv.y << 16), x3 = __uint_as_float(xv.y & 0xFFFF0000u);
-        *reinterpret_cast<uint2*>(dst + 8 * r4) = make_uint2(pack2_bf16(x0 + acc[4 * r4], x1 + acc[4 * r4 + 1]),
-                                                              pack2_bf16(x2 + acc[4 * r4 + 2], x3 + acc[4 * r4 + 3]));
+      for (int r4 = 0; r4 < 4; ++r4)
+        *reinterpret_cast<float4*>(otf + li * (kOutStride / 2) + 8 * r4 + 4 * g) =
+            make_float4(acc[4 * r4], acc[4 * r4 + 1], acc[4 * r4 + 2], acc[4 * r4 + 3]);
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2) {
+        const float* src = otf + ((lane >> 2) + 16 * h2) * (kOutStride / 2) + 8 * (lane & 3);
+        const float4 p0 = *reinterpret_cast<const float4*>(src), p1 = *reinterpret_cast<const float4*>(src + 4);
+        if (!ok2[h2]) continue;
+        const uint64_t at = row2[h2] * KD + n0 + 8 * (lane & 3);
+        float xv[8];
+        unpack8(*reinterpret_cast<const uint4*>(a.resid + at), xv);
+        *reinterpret_cast<uint4*>(a.y + at) = make_uint4(pack2_bf16(xv[0] + p0.x, xv[1] + p0.y), pack2_bf16(xv[2] + p0.z, xv[3] + p0.w),
+                                                        pack2_bf16(xv[4] + p1.x, xv[5] + p1.y), pack2_bf16(xv[6] + p1.z, xv[7] + p1.w));
       }
     }
   };
