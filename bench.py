@@ -29,6 +29,13 @@ CONFIGS = {
                 batch=64, mean_len=2048, min_len=64, max_len=8192, zipf=1.0, n_time=32, warm_batches=20,
                 desc="Mid: 4 layers d=256 H=4 bf16, table 10Mx256 bf16 pinned host, 64 GiB pool @ EMB:KV=0.5, "
                      "batch 64 lognormal(mean 2048, max 8192) histories, Zipf(1.0), KV page 64 tokens"),
+    # EMB-heavy: lookups only (8 sparse features per token, sum-pooled); shows the gather against HBM proper,
+    # since a batch touches far more bytes than the caches hold
+    "embheavy": dict(index=3, L=4, d=128, H=2, bf16=True, rows=100_000_000, pool_bytes=50 << 30, pt=64, alpha=0.8,
+                     batch=256, mean_len=1024, min_len=1024, max_len=1024, zipf=0.8, n_time=32, warm_batches=3,
+                     bag=8, emb_only=True,
+                     desc="EMB-heavy: table 100Mx128 bf16 pinned host, 50 GiB pool @ EMB:KV=0.8 (40 GiB hot cache), "
+                          "batch 256 x 1024 tokens x 8 features sum-pooled, Zipf(0.8); lookups only"),
     "tiny": dict(index=0, L=1, d=64, H=2, bf16=False, rows=100_000, pool_bytes=4 << 20, pt=16, alpha=0.5,
                  batch=4, mean_len=256, min_len=256, max_len=256, zipf=1.0, n_time=32, warm_batches=4,
                  desc="Tiny: 1 layer d=64 H=2 fp32, table 100k x 64 fp32, 4 MiB pool, 4 x 256 tokens, KV page 16"),
@@ -88,6 +95,71 @@ def build_workload(c, torch, Hn, B, synth):
     wl["x"] = torch.empty((N, d), dtype=Hn.torch_dtype(elem), device=dev)
     wl["out"] = torch.empty((N, d), dtype=Hn.torch_dtype(elem), device=dev)
     return wl
+
+
+def emb_only_bench(args, c, torch, Hn, B, synth):
+    """Lookups only (pooled): whole emb_lookup calls per second and the probe+gather kernel against HBM."""
+    dev = Hn.DEV
+    d, pt, L, bag = c["d"], c["pt"], c["L"], c["bag"]
+    table = torch.empty((c["rows"], d), dtype=torch.int16, pin_memory=True)
+    synth.fill_table_bf16_torch(table, synth.SEED_BASE + c["index"], dev)
+    torch.cuda.synchronize()
+    page_size = pt * 2 * L * d * 2
+    n_pages = c["pool_bytes"] // page_size
+    pool = Hn.Pool(n_pages, page_size, d * 2, B.ELEM_BF16, pt, 32, table.view(torch.bfloat16), c["alpha"])
+    rng = synth.rng_for(c["index"], 11)
+    tokens = c["batch"] * c["mean_len"]
+    n_sets = c["warm_batches"] + args.warmup + args.steps
+    out = torch.empty((tokens, d), dtype=torch.bfloat16, device=dev)
+    ids_dev = []
+    for k in range(n_sets):
+        ids_dev.append(torch.from_numpy(synth.multi_feature_ids(rng, c["rows"], bag, c["zipf"], tokens)).to(dev))
+    # The hot cache of this configuration holds more slots than the table has rows, so its steady state is a
+    # cache that has seen every row: reach it with one sweep over all ids (about the table's size over PCIe)
+    # instead of thousands of Zipf batches, then settle with Zipf batches.
+    per = tokens * bag
+    for lo in range(0, c["rows"], per):
+        sweep = torch.arange(lo, lo + per, dtype=torch.int64, device=dev) % c["rows"]
+        rc = B.emb_lookup(pool.h, sweep, out, bag, None)
+        assert rc == B.OK, (rc, B.last_error())
+    for k in range(c["warm_batches"] + args.warmup):
+        rc = B.emb_lookup(pool.h, ids_dev[k], out, bag, None)
+        assert rc == B.OK, (rc, B.last_error())
+    torch.cuda.synchronize()
+    st0 = pool.stats()
+    B.racer_prof_enable(pool.h, 1)
+    B.racer_prof_read(pool.h)
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        rc = B.emb_lookup(pool.h, ids_dev[c["warm_batches"] + args.warmup + k], out, bag, None)
+        assert rc == B.OK, (rc, B.last_error())
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = B.racer_prof_read(pool.h)
+    B.racer_prof_enable(pool.h, 0)
+    st1 = pool.stats()
+    lookups = st1["lookups"] - st0["lookups"]
+    hits = st1["hits"] - st0["hits"]
+    R = d * 2
+    ways = st1["pages_emb"] / (n_pages / 32)
+    # id + tag line + stamp per lookup, the row read of every hit, the pooled rows written
+    gather_bytes = (lookups * (8 + 4 * ways + 4) + hits * R) / args.steps + tokens * R
+    gather_ms = prof["emb_gather"][0] / max(prof["emb_gather"][1], 1)
+    gbs = gather_bytes / (gather_ms * 1e-3) / 1e9 if gather_ms > 0 else 0.0
+    ms = dt * 1e3 / args.steps
+    result = {
+        "metric": "emb_lookup_tokens_per_s", "value": tokens / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": c["desc"], "tokens_per_step": tokens, "lookups_per_step": tokens * bag,
+                   "hit_rate": hits / max(lookups, 1), "unique_misses_per_step": (st1["unique_misses"] - st0["unique_misses"]) / args.steps},
+        "roofline": {"kernel": "emb_probe_gather", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": gbs / PEAK_HBM_GBS, "traffic": None, "bytes_per_launch": gather_bytes, "ms_per_launch": gather_ms},
+        "kernels": {k: {"ms_per_launch": (v[0] / v[1] if v[1] else 0.0), "launches_per_step": v[1] / args.steps}
+                    for k, v in prof.items() if v[1]},
+    }
+    print(json.dumps(result))
+    pool.close()
 
 
 def one_step(wl, k, B):
@@ -163,6 +235,9 @@ def main():
 
     B.load()
     c = CONFIGS[args.config]
+    if c.get("emb_only"):
+        emb_only_bench(args, c, torch, Hn, B, synth)
+        return
     wl = build_workload(c, torch, Hn, B, synth)
     pool = wl["pool"]
     # warm the EMB cache, then whole warm-up steps

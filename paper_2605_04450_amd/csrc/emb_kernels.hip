@@ -349,6 +349,157 @@ __global__ __launch_bounds__(256) void emb_probe_gather_w32(EmbView v, MissWs ws
 }
 
 // ---------------------------------------------------------------------------------------
+// The same probe for pooled lookups (bag = 2, 4 or 8 consecutive lookups summed into one output
+// row): a wavefront's eight lookups are 8 / bag whole bags.  The rows of the hits pass
+// through a wave-private LDS tile, from which every lane sums its 4-byte word of an output
+// row over the bag's members in order, in fp32, and rounds once (the definition of the pooled
+// row).  A bag with a missing member is left to the miss path, as in the generic kernel.
+// ---------------------------------------------------------------------------------------
+template <int PASSES>  // row_bytes / 128
+__global__ __launch_bounds__(256) void emb_probe_gather_w32_bag(EmbView v, MissWs ws, const int64_t* __restrict__ ids,
+                                                                uint32_t n, uint32_t bag, uint8_t* __restrict__ out,
+                                                                uint8_t* __restrict__ hit_flags, uint32_t batch) {
+  constexpr uint32_t kRounds = 4;
+  constexpr uint32_t kPerBlock = 32 * kRounds;  // lookups per block: 4 waves x 8 groups x rounds
+  constexpr uint32_t kRowWords = PASSES * 32;   // 4-byte words per row
+  __shared__ uint32_t s_miss[kPerBlock], s_def[kPerBlock];
+  __shared__ uint32_t s_n[2], s_base[2];
+  __shared__ uint32_t s_cnt[3];
+  __shared__ __attribute__((aligned(16))) uint32_t s_rows[4][8][kRowWords];
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, grp = lane >> 3, j = lane & 7;
+  if (tid < 2) s_n[tid] = 0;
+  if (tid < 3) s_cnt[tid] = 0;
+  if (blockIdx.x == 0 && tid < 3) ws.ctr_next[tid] = 0;  // the next call's list counters
+  __syncthreads();
+  const uint4* tags4 = reinterpret_cast<const uint4*>(v.tags);
+  const bool bf16 = v.elem == 1;
+  // The three dependent memory steps (ids -> tag lines -> rows) are taken for all rounds at once, so that a
+  // wavefront has 32 independent lookups in flight per step instead of eight.
+  uint64_t i0[kRounds];
+  bool active[kRounds], valid[kRounds];
+  uint32_t id32[kRounds], set[kRounds], nw[kRounds];
+  uint4 tag[kRounds];
+#pragma unroll
+  for (uint32_t r = 0; r < kRounds; ++r) {
+    i0[r] = static_cast<uint64_t>(blockIdx.x) * kPerBlock + (r * 4 + wave) * 8;  // n % bag == 0, 8 % bag == 0
+    active[r] = i0[r] + grp < n;
+  }
+  int64_t id[kRounds];
+#pragma unroll
+  for (uint32_t r = 0; r < kRounds; ++r) id[r] = active[r] ? ids[i0[r] + grp] : -1;
+#pragma unroll
+  for (uint32_t r = 0; r < kRounds; ++r) {
+    valid[r] = active[r] && id[r] >= 0 && static_cast<uint64_t>(id[r]) < v.rows;
+    id32[r] = static_cast<uint32_t>(id[r]);
+    set[r] = valid[r] ? set_of(v, id[r]) : 0;
+    nw[r] = valid[r] ? ways_of(v, set[r]) : 0;
+    tag[r] = make_uint4(0, 0, 0, 0);
+    if (4 * j < nw[r]) tag[r] = tags4[static_cast<uint64_t>(set[r]) * 8 + j];
+  }
+  uint32_t n_hit = 0, n_valid = 0, n_invalid = 0;  // counted by lane 0 of each group
+  bool hit[kRounds], miss[kRounds];
+  int64_t loc[kRounds];
+  uint4 row[kRounds][PASSES];
+#pragma unroll
+  for (uint32_t r = 0; r < kRounds; ++r) {
+    uint32_t cand = 255;  // lowest matching way seen by this lane
+    if (4 * j < nw[r]) {
+      const uint4 t = tag[r];
+      if (4 * j + 3 < nw[r] && t.w == id32[r]) cand = 4 * j + 3;
+      if (4 * j + 2 < nw[r] && t.z == id32[r]) cand = 4 * j + 2;
+      if (4 * j + 1 < nw[r] && t.y == id32[r]) cand = 4 * j + 1;
+      if (t.x == id32[r]) cand = 4 * j;
+    }
+#pragma unroll
+    for (int o = 4; o > 0; o >>= 1) {
+      const uint32_t other = __shfl_xor(cand, o, kWave);
+      cand = other < cand ? other : cand;
+    }
+    hit[r] = valid[r] && cand != 255;
+    miss[r] = valid[r] && !hit[r];
+    // the member's row (zeros for an invalid id or a miss)
+    loc[r] = miss[r] ? -2 : -1;  // -2: replaced by the staging row once the miss is resolved
+#pragma unroll
+    for (int c = 0; c < PASSES; ++c) row[r][c] = make_uint4(0, 0, 0, 0);
+    if (hit[r]) {
+      loc[r] = slot_offset(v, set[r], cand);
+      const uint8_t* src = v.base + loc[r];
+#pragma unroll
+      for (int c = 0; c < PASSES; ++c) row[r][c] = *reinterpret_cast<const uint4*>(src + 16 * (j + 8 * c));
+    }
+    if (j == 0) {
+      n_hit += hit[r];
+      n_valid += valid[r];
+      n_invalid += active[r] && !valid[r];
+    }
+    const uint32_t way = hit[r] ? cand : 0;
+    set[r] = set[r] * 32 + way;  // from here on: the stamp index
+  }
+#pragma unroll
+  for (uint32_t r = 0; r < kRounds; ++r) {
+    const uint64_t i = i0[r] + grp;
+    if (j == 0) {
+      if (hit[r]) v.stamps[set[r]] = batch;
+      if (hit_flags && active[r]) hit_flags[i] = hit[r] ? 1 : 0;
+    }
+#pragma unroll
+    for (int c = 0; c < PASSES; ++c) *reinterpret_cast<uint4*>(&s_rows[wave][grp][4 * (j + 8 * c)]) = row[r][c];
+    // a bag with a missing member waits for the miss path, which needs every member's location
+    const unsigned long long miss_m = __ballot(miss[r]);  // eight equal bits per group
+    const uint32_t bag_first = (grp / bag) * bag;
+    const unsigned long long bag_mask = bag == 8 ? ~0ull : (1ull << (8 * bag)) - 1ull;
+    const bool deferred = active[r] && ((miss_m >> (8 * bag_first)) & bag_mask) != 0;
+    if (j == 0) {
+      if (deferred) ws.loc[i] = loc[r];
+      if (miss[r]) s_miss[atomicAdd(&s_n[0], 1u)] = static_cast<uint32_t>(i);
+      if (deferred && grp == bag_first) s_def[atomicAdd(&s_n[1], 1u)] = static_cast<uint32_t>(i / bag);
+    }
+    // ordered sums: word w of the wavefront's output rows
+    const uint32_t out_words = kRowWords * (8 / bag);
+    for (uint32_t w = lane; w < out_words; w += 64) {
+      const uint32_t orow = w / kRowWords, word = w % kRowWords, first = orow * bag;
+      if (i0[r] + first >= n || ((miss_m >> (8 * first)) & bag_mask) != 0) continue;
+      uint32_t res;
+      if (bf16) {
+        float a0 = 0.0f, a1 = 0.0f;
+        for (uint32_t f = 0; f < bag; ++f) {
+          const uint32_t x = s_rows[wave][first + f][word];
+          const float v0 = bf16_to_f32(x & 0xFFFFu), v1 = bf16_to_f32(x >> 16);
+          a0 = f == 0 ? v0 : a0 + v0;
+          a1 = f == 0 ? v1 : a1 + v1;
+        }
+        res = f32_to_bf16(a0) | (f32_to_bf16(a1) << 16);
+      } else {
+        float a0 = 0.0f;
+        for (uint32_t f = 0; f < bag; ++f) {
+          const float v0 = __uint_as_float(s_rows[wave][first + f][word]);
+          a0 = f == 0 ? v0 : a0 + v0;
+        }
+        res = __float_as_uint(a0);
+      }
+      reinterpret_cast<uint32_t*>(out + ((i0[r] + first) / bag) * v.row_bytes)[word] = res;
+    }
+  }
+  if (j == 0) {
+    if (n_hit) atomicAdd(&s_cnt[0], n_hit);
+    if (n_valid) atomicAdd(&s_cnt[1], n_valid);
+    if (n_invalid) atomicAdd(&s_cnt[2], n_invalid);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    s_base[0] = s_n[0] ? atomicAdd(&ws.ctr[0], s_n[0]) : 0;
+    s_base[1] = s_n[1] ? atomicAdd(&ws.ctr[1], s_n[1]) : 0;
+    if (s_cnt[1]) atomicAdd(&v.counters[ctr_index(kCtrLookups)], static_cast<unsigned long long>(s_cnt[1]));
+    if (s_cnt[0]) atomicAdd(&v.counters[ctr_index(kCtrHits)], static_cast<unsigned long long>(s_cnt[0]));
+    if (s_cnt[1] - s_cnt[0]) atomicAdd(&v.counters[ctr_index(kCtrMisses)], static_cast<unsigned long long>(s_cnt[1] - s_cnt[0]));
+    if (s_cnt[2]) atomicAdd(&v.counters[ctr_index(kCtrInvalid)], static_cast<unsigned long long>(s_cnt[2]));
+  }
+  __syncthreads();
+  for (uint32_t k = tid; k < s_n[0]; k += 256) ws.miss_list[s_base[0] + k] = s_miss[k];
+  for (uint32_t k = tid; k < s_n[1]; k += 256) ws.def_list[s_base[1] + k] = s_def[k];
+}
+
+// ---------------------------------------------------------------------------------------
 // Miss path.  All kernels read the list lengths from device memory and return at once
 // when the batch had no miss.
 // ---------------------------------------------------------------------------------------
@@ -624,6 +775,16 @@ hipError_t launch_emb_probe(const EmbView& v, const MissWs& ws, const int64_t* i
       RACER_W32_CASE(1) RACER_W32_CASE(2) RACER_W32_CASE(3) RACER_W32_CASE(4)
       RACER_W32_CASE(5) RACER_W32_CASE(6) RACER_W32_CASE(7) RACER_W32_CASE(8)
 #undef RACER_W32_CASE
+    }
+    return hipGetLastError();
+  }
+  if ((bag == 2 || bag == 4 || bag == 8) && v.w_max == 32 && v.row_bytes % 128 == 0 && v.row_bytes <= 512) {
+    const dim3 grid((n + 127) / 128), block(256);  // 128 lookups per block
+    switch (v.row_bytes / 128) {
+#define RACER_W32_BAG_CASE(P) \
+  case P: hipLaunchKernelGGL(emb_probe_gather_w32_bag<P>, grid, block, 0, stream, v, ws, ids, n, bag, out, hit_flags, batch); break;
+      RACER_W32_BAG_CASE(1) RACER_W32_BAG_CASE(2) RACER_W32_BAG_CASE(3) RACER_W32_BAG_CASE(4)
+#undef RACER_W32_BAG_CASE
     }
     return hipGetLastError();
   }

@@ -215,8 +215,10 @@ def test_outputs_do_not_depend_on_page_placement_or_page_size():
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
 
 
-def test_bad_page_ids_are_skipped_and_counted():
-    c = Case(6, 1, 64, 2, 16, False, 64, 8, 64.0, 64)
+@pytest.mark.parametrize("bf16,d", [(False, 64), (True, 128), (True, 64)])
+def test_bad_page_ids_are_skipped_and_counted(bf16, d):
+    # fp32 kernels, the fused bf16 layer halves (d = 128) and the separate bf16 LayerNorm + GEMM kernels (d = 64)
+    c = Case(6, 1, d, d // 64 if bf16 else 2, 16, bf16, 64, 8, 64.0, 64)
     reqs, pts, ts, x = c.inputs([0], [40])
     bad = pts.copy()
     bad[1] = 10**6
