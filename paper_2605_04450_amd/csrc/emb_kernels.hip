@@ -263,11 +263,12 @@ __global__ __launch_bounds__(256) void emb_probe_gather(EmbView v, MissWs ws, co
 // row with 16-byte lanes, so a wavefront keeps eight independent lookups in flight per
 // instruction and nothing is serialised over the lookups of a batch.
 // ---------------------------------------------------------------------------------------
+constexpr uint32_t kW32Rounds = 2;  // lookups per group of eight lanes (more leaves too few blocks for a Mid-sized batch)
 template <int PASSES>  // row_bytes / 128
 __global__ __launch_bounds__(256) void emb_probe_gather_w32(EmbView v, MissWs ws, const int64_t* __restrict__ ids,
                                                             uint32_t n, uint8_t* __restrict__ out,
                                                             uint8_t* __restrict__ hit_flags, uint32_t batch) {
-  constexpr uint32_t kRounds = 2;
+  constexpr uint32_t kRounds = kW32Rounds;
   constexpr uint32_t kPerBlock = 32 * kRounds;  // lookups per block: 4 waves x 8 groups x rounds
   __shared__ uint32_t s_miss[kPerBlock];
   __shared__ uint32_t s_n, s_base_m, s_base_d;
@@ -278,22 +279,39 @@ __global__ __launch_bounds__(256) void emb_probe_gather_w32(EmbView v, MissWs ws
   if (blockIdx.x == 0 && tid < 3) ws.ctr_next[tid] = 0;  // the next call's list counters
   __syncthreads();
   const uint4* tags4 = reinterpret_cast<const uint4*>(v.tags);
-  uint32_t n_hit = 0, n_valid = 0, n_invalid = 0;  // counted by lane 0 of each group
+  // The dependent memory steps (ids -> tag lines -> rows -> output) are each taken for all rounds at once:
+  // a wavefront has 8 * kRounds independent lookups in flight per step.
+  uint64_t idx[kRounds];
+  bool active[kRounds], valid[kRounds];
+  int64_t id[kRounds];
+  uint32_t set[kRounds], nw[kRounds];
+  uint4 tag[kRounds];
 #pragma unroll
-  for (uint32_t round = 0; round < kRounds; ++round) {
-    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * kPerBlock + (round * 4 + wave) * 8 + grp;
-    const bool active = i < n;
-    const int64_t id = active ? ids[i] : -1;
-    const bool valid = active && id >= 0 && static_cast<uint64_t>(id) < v.rows;
-    const uint32_t id32 = static_cast<uint32_t>(id);
-    const uint32_t set = valid ? set_of(v, id) : 0;
-    const uint32_t nw = valid ? ways_of(v, set) : 0;
+  for (uint32_t r = 0; r < kRounds; ++r) {
+    idx[r] = static_cast<uint64_t>(blockIdx.x) * kPerBlock + (r * 4 + wave) * 8 + grp;
+    active[r] = idx[r] < n;
+    id[r] = active[r] ? ids[idx[r]] : -1;
+  }
+#pragma unroll
+  for (uint32_t r = 0; r < kRounds; ++r) {
+    valid[r] = active[r] && id[r] >= 0 && static_cast<uint64_t>(id[r]) < v.rows;
+    set[r] = valid[r] ? set_of(v, id[r]) : 0;
+    nw[r] = valid[r] ? ways_of(v, set[r]) : 0;
+    tag[r] = make_uint4(0, 0, 0, 0);
+    if (4 * j < nw[r]) tag[r] = tags4[static_cast<uint64_t>(set[r]) * 8 + j];
+  }
+  uint32_t n_hit = 0, n_valid = 0, n_invalid = 0;  // counted by lane 0 of each group
+  bool hit[kRounds];
+  uint4 row[kRounds][PASSES];
+#pragma unroll
+  for (uint32_t r = 0; r < kRounds; ++r) {
+    const uint32_t id32 = static_cast<uint32_t>(id[r]);
     uint32_t cand = 255;  // lowest matching way seen by this lane
-    if (4 * j < nw) {
-      const uint4 t = tags4[static_cast<uint64_t>(set) * 8 + j];
-      if (4 * j + 3 < nw && t.w == id32) cand = 4 * j + 3;
-      if (4 * j + 2 < nw && t.z == id32) cand = 4 * j + 2;
-      if (4 * j + 1 < nw && t.y == id32) cand = 4 * j + 1;
+    if (4 * j < nw[r]) {
+      const uint4 t = tag[r];
+      if (4 * j + 3 < nw[r] && t.w == id32) cand = 4 * j + 3;
+      if (4 * j + 2 < nw[r] && t.z == id32) cand = 4 * j + 2;
+      if (4 * j + 1 < nw[r] && t.y == id32) cand = 4 * j + 1;
       if (t.x == id32) cand = 4 * j;
     }
 #pragma unroll
@@ -301,29 +319,33 @@ __global__ __launch_bounds__(256) void emb_probe_gather_w32(EmbView v, MissWs ws
       const uint32_t other = __shfl_xor(cand, o, kWave);
       cand = other < cand ? other : cand;
     }
-    const bool hit = valid && cand != 255;
-    const bool miss = valid && !hit;
-    if (j == 0) {
-      n_hit += hit;
-      n_valid += valid;
-      n_invalid += active && !valid;
-      if (hit_flags && active) hit_flags[i] = hit ? 1 : 0;
+    hit[r] = valid[r] && cand != 255;
+#pragma unroll
+    for (int c = 0; c < PASSES; ++c) row[r][c] = make_uint4(0, 0, 0, 0);
+    if (hit[r]) {
+      const uint8_t* src = v.base + slot_offset(v, set[r], cand);
+#pragma unroll
+      for (int c = 0; c < PASSES; ++c) row[r][c] = *reinterpret_cast<const uint4*>(src + 16 * (j + 8 * c));
     }
-    uint8_t* dst = out + i * v.row_bytes;
-    if (hit) {
-      if (j == 0) v.stamps[static_cast<uint64_t>(set) * 32 + cand] = batch;
-      const uint8_t* src = v.base + slot_offset(v, set, cand);
-      uint4 r[PASSES];
+    set[r] = set[r] * 32 + (hit[r] ? cand : 0);  // from here on: the stamp index
+  }
 #pragma unroll
-      for (int c = 0; c < PASSES; ++c) r[c] = *reinterpret_cast<const uint4*>(src + 16 * (j + 8 * c));
+  for (uint32_t r = 0; r < kRounds; ++r) {
+    const bool miss = valid[r] && !hit[r];
+    if (j == 0) {
+      n_hit += hit[r];
+      n_valid += valid[r];
+      n_invalid += active[r] && !valid[r];
+      if (hit_flags && active[r]) hit_flags[idx[r]] = hit[r] ? 1 : 0;
+      if (hit[r]) v.stamps[set[r]] = batch;
+    }
+    uint8_t* dst = out + idx[r] * v.row_bytes;
+    if (hit[r] || (active[r] && !valid[r])) {  // the row, or zeros for an id outside the table
 #pragma unroll
-      for (int c = 0; c < PASSES; ++c) *reinterpret_cast<uint4*>(dst + 16 * (j + 8 * c)) = r[c];
-    } else if (active && !valid) {
-#pragma unroll
-      for (int c = 0; c < PASSES; ++c) *reinterpret_cast<uint4*>(dst + 16 * (j + 8 * c)) = make_uint4(0, 0, 0, 0);
+      for (int c = 0; c < PASSES; ++c) *reinterpret_cast<uint4*>(dst + 16 * (j + 8 * c)) = row[r][c];
     } else if (miss && j == 0) {
-      ws.loc[i] = -2;  // replaced by the staging row once the miss is resolved
-      s_miss[atomicAdd(&s_n, 1u)] = static_cast<uint32_t>(i);
+      ws.loc[idx[r]] = -2;  // replaced by the staging row once the miss is resolved
+      s_miss[atomicAdd(&s_n, 1u)] = static_cast<uint32_t>(idx[r]);
     }
   }
   if (j == 0) {
@@ -768,7 +790,8 @@ hipError_t launch_emb_probe(const EmbView& v, const MissWs& ws, const int64_t* i
                             uint8_t* out, uint8_t* hit_flags, uint32_t batch, hipStream_t stream) {
   if (n == 0) return hipSuccess;
   if (bag == 1 && v.w_max == 32 && v.row_bytes % 128 == 0 && v.row_bytes <= 1024) {
-    const dim3 grid((n + 63) / 64), block(256);  // 64 lookups per block
+    const uint32_t per_block = 32 * kW32Rounds;
+    const dim3 grid((n + per_block - 1) / per_block), block(256);
     switch (v.row_bytes / 128) {
 #define RACER_W32_CASE(P) \
   case P: hipLaunchKernelGGL(emb_probe_gather_w32<P>, grid, block, 0, stream, v, ws, ids, n, out, hit_flags, batch); break;
