@@ -89,13 +89,13 @@ def test_small_caches_under_pressure(n_pages, spp, w_max, frac, alphabet, batch)
 
 
 @pytest.mark.parametrize("d,bag,n", [(128, 8, 8 * 3001), (256, 1, 20011), (512, 1, 5000), (64, 4, 4 * 999),
-                                     (256, 3, 3 * 1000), (128, 64, 64 * 40)])
+                                     (256, 3, 3 * 1000), (128, 64, 64 * 40), (192, 2, 2 * 1501), (256, 4, 4 * 777)])
 def test_bf16_rows_and_pooling(d, bag, n):
     rng = np.random.default_rng(d + bag)
     rows = 200000
     table = np.zeros((rows, d), dtype=np.uint16)
     synth.fill_table_bf16(table, seed=d)
-    page_size = 64 * 1024
+    page_size = 64 * 1024 if (64 * 1024) % (2 * d) == 0 else 128 * 2 * d  # a whole number of rows per page
     pool, orc = make_pair(256, page_size, d, True, 16, 32, table, 0.5)
     batches = [synth.zipf_ids(rng, rows, 0.9, n) for _ in range(4)]
     run_batches(pool, orc, table, batches, bag=bag, tag="bf16")
@@ -114,6 +114,24 @@ def test_invalid_ids_duplicates_and_empty_batch():
     b1 = np.array([1, -5, 3, 4, 2000, 6, 1, 1], dtype=np.int64)
     run_batches(pool, orc, table, [b1], bag=4, tag="edge-bag")
     pool.close()
+
+
+def test_pooled_fast_kernel_edge_cases_fp32_rows():
+    # rows of 128 bytes (fp32, d = 32): bags of 2, 4 and 8 go through the eight-lanes-per-lookup pooled kernel;
+    # invalid members add zeros, bags with a missing member wait for the miss path, the last wavefront is ragged
+    rng = np.random.default_rng(15)
+    table = rng.standard_normal((5000, 32)).astype(np.float32)
+    for bag in (2, 4, 8):
+        pool, orc = make_pair(64, 4096, 32, False, 4, 32, table, 0.5)
+        ids = rng.integers(0, 5000, size=bag * 37).astype(np.int64)
+        ids[3] = -1
+        ids[bag * 5] = 10**9
+        ids[bag * 9: bag * 10] = -7          # a bag of invalid ids only: a zero row
+        warm = ids.copy()
+        warm[::3] = rng.integers(0, 5000, size=len(warm[::3]))  # second batch: a mix of hits and misses inside bags
+        run_batches(pool, orc, table, [ids, warm, ids, np.zeros(0, dtype=np.int64), ids[: bag * 3]], bag=bag,
+                    tag="pooled-edge-%d" % bag)
+        pool.close()
 
 
 def test_same_inputs_twice_give_identical_state():
