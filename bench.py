@@ -36,6 +36,12 @@ CONFIGS = {
                      bag=8, emb_only=True,
                      desc="EMB-heavy: table 100Mx128 bf16 pinned host, 50 GiB pool @ EMB:KV=0.8 (40 GiB hot cache), "
                           "batch 256 x 1024 tokens x 8 features sum-pooled, Zipf(0.8); lookups only"),
+    # Long history with KV reuse: the attention kernel alone (one layer) on 512 new tokens per request against a
+    # 16k-token cached prefix held in shuffled pages
+    "longreuse": dict(index=2, L=8, d=512, H=8, bf16=True, pt=64, batch=32, prefix=16384, new=512, n_time=32,
+                      attn_only=True,
+                      desc="Long history KV reuse: 8 layers d=512 H=8 bf16, 32 requests x (16384 cached + 512 new) tokens, "
+                           "KV page 64 tokens; paged attention of one layer only"),
     "tiny": dict(index=0, L=1, d=64, H=2, bf16=False, rows=100_000, pool_bytes=4 << 20, pt=16, alpha=0.5,
                  batch=4, mean_len=256, min_len=256, max_len=256, zipf=1.0, n_time=32, warm_batches=4,
                  desc="Tiny: 1 layer d=64 H=2 fp32, table 100k x 64 fp32, 4 MiB pool, 4 x 256 tokens, KV page 16"),
@@ -162,6 +168,77 @@ def emb_only_bench(args, c, torch, Hn, B, synth):
     pool.close()
 
 
+def attn_only_bench(args, c, torch, Hn, B, synth):
+    """The attention kernel of one layer on cached prefixes (synthetic K,V written straight into shuffled pages)."""
+    dev = Hn.DEV
+    L, d, H, pt, P, T, Bq = c["L"], c["d"], c["H"], c["pt"], c["prefix"], c["new"], c["batch"]
+    n_pos = P + T
+    rng = synth.rng_for(c["index"])
+    w = synth.make_weights(rng, L, d, H, n_pos, c["n_time"], True)
+    model = Hn.Model(L, d, H, B.ELEM_BF16, pt, n_pos, c["n_time"], float(n_pos), w)
+    page = model.page_size()
+    pages_per_req = (P + T + pt - 1) // pt
+    n_pages = ((Bq * pages_per_req * 4 // 3) // 32 + 1) * 32
+    pool = Hn.Pool(n_pages, page, d * 2, B.ELEM_BF16, pt, 32, None, 0.25)
+    first_kv = n_pages // 4
+    perm = first_kv + rng.permutation(n_pages - first_kv)
+    reqs, n_pt, n_ts, N = synth.make_requests([P] * Bq, [T] * Bq, pt)
+    pts = perm[:n_pt].astype(np.int32)
+    ts = np.concatenate([synth.timestamps(rng, P + T) for _ in range(Bq)])
+    layer = 3
+    mem = pool.mem.view(torch.bfloat16)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+    for r in range(Bq):
+        k = (torch.randn((P + T, d), generator=gen, device=dev) * (64 ** -0.25)).to(torch.bfloat16)
+        v = torch.randn((P + T, d), generator=gen, device=dev).to(torch.bfloat16)
+        pg = pts[reqs[r][2]: reqs[r][2] + pages_per_req]
+        vblocks = v.view(pages_per_req, pt, H, 64).permute(0, 2, 3, 1).contiguous()   # [page][head][d_h][token]
+        kblocks = k.view(pages_per_req, pt, H, 64).permute(0, 2, 1, 3).contiguous()   # [page][head][token][d_h]
+        base = torch.from_numpy(pg.astype(np.int64)).to(dev) * (page // 2)
+        idx = base[:, None] + torch.arange(pt * 64, device=dev)[None, :]
+        for h in range(H):
+            mem[(idx + Hn.kv_block_elem_offset(L, d, H, pt, 0, layer, 0, h)).reshape(-1)] = kblocks[:, h].reshape(-1)
+            mem[(idx + Hn.kv_block_elem_offset(L, d, H, pt, 0, layer, 1, h)).reshape(-1)] = vblocks[:, h].reshape(-1)
+    q = torch.randn((N, d), generator=gen, device=dev).to(torch.bfloat16)
+    o = torch.empty_like(q)
+    pts_dev, ts_dev = torch.from_numpy(pts).to(dev), torch.from_numpy(ts).to(dev)
+
+    def call():
+        rc = B.hstu_attn_paged(pool.h, model.h, layer, reqs, pts_dev, q, ts_dev, o)
+        assert rc == B.OK, (rc, B.last_error())
+    for _ in range(args.warmup):
+        call()
+    torch.cuda.synchronize()
+    B.racer_prof_enable(pool.h, 1)
+    B.racer_prof_read(pool.h)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        call()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = B.racer_prof_read(pool.h)
+    B.racer_prof_enable(pool.h, 0)
+    pairs = float(Bq) * (T * P + T * (T + 1) / 2)
+    flop = 4.0 * d * pairs
+    attn_ms = prof["attention"][0] / max(prof["attention"][1], 1)
+    tf = flop / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else 0.0
+    ms = dt * 1e3 / args.steps
+    print(json.dumps({
+        "metric": "hstu_attention_tokens_per_s", "value": N / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": c["desc"], "new_tokens_per_step": int(N), "causal_pairs": pairs},
+        "roofline": {"kernel": "attention_bf16_mfma", "bound": "mfma", "achieved": tf, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": tf / PEAK_BF16_TFLOPS, "traffic": None, "flop_per_launch": flop,
+                     "ms_per_launch": attn_ms},
+        "kernels": {k: {"ms_per_launch": (v[0] / v[1] if v[1] else 0.0), "launches_per_step": v[1] / args.steps}
+                    for k, v in prof.items() if v[1]},
+    }))
+    model.close()
+    pool.close()
+
+
 def one_step(wl, k, B):
     ids = wl["ids_dev"][k % len(wl["ids_dev"])]
     rc = B.emb_lookup(wl["pool"].h, ids, wl["x"], 1, None)
@@ -237,6 +314,9 @@ def main():
     c = CONFIGS[args.config]
     if c.get("emb_only"):
         emb_only_bench(args, c, torch, Hn, B, synth)
+        return
+    if c.get("attn_only"):
+        attn_only_bench(args, c, torch, Hn, B, synth)
         return
     wl = build_workload(c, torch, Hn, B, synth)
     pool = wl["pool"]
