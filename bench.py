@@ -5,7 +5,7 @@ table 10M x 256 bf16 in pinned host memory; 64 GiB HBM pool of 256 KiB pages (64
 at EMB:KV = 0.5; batch of 64 requests with lognormal history lengths (mean 2048, max 8192);
 Zipf(1.0) ids; every request is prefilled through its page table (prefix 0).
 
-Prints ONE JSON line (see README/DESIGN for the fields).  `--config tiny` runs the small fp32
+Prints ONE JSON line.  `--config tiny` runs the small fp32
 configuration instead (used for quick checks).
 """
 import argparse
