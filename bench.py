@@ -42,6 +42,12 @@ CONFIGS = {
                       attn_only=True,
                       desc="Long history KV reuse: 8 layers d=512 H=8 bf16, 32 requests x (16384 cached + 512 new) tokens, "
                            "KV page 64 tokens; paged attention of one layer only"),
+    # Split sweep: the boundary moves in steps of 0.05 down from 0.8 to 0.2 (each step evicts and compacts the
+    # hot cache) and back up (metadata only), with lookup batches after every move
+    "sweep": dict(index=4, L=4, d=256, H=4, bf16=True, rows=100_000_000, pool_bytes=128 << 30, pt=64, alpha=0.8,
+                  batch=128, mean_len=3072, min_len=512, max_len=12288, zipf=0.9, n_time=32, split_sweep=True,
+                  desc="Split sweep: 128 GiB pool, table 100Mx256 bf16 pinned host, EMB:KV 0.8 -> 0.2 -> 0.8 in steps of "
+                       "0.05 with page remap/eviction, batches of 128 lognormal(512..12k) histories, Zipf(0.9) ids"),
     "tiny": dict(index=0, L=1, d=64, H=2, bf16=False, rows=100_000, pool_bytes=4 << 20, pt=16, alpha=0.5,
                  batch=4, mean_len=256, min_len=256, max_len=256, zipf=1.0, n_time=32, warm_batches=4,
                  desc="Tiny: 1 layer d=64 H=2 fp32, table 100k x 64 fp32, 4 MiB pool, 4 x 256 tokens, KV page 16"),
@@ -239,6 +245,74 @@ def attn_only_bench(args, c, torch, Hn, B, synth):
     pool.close()
 
 
+def split_sweep_bench(args, c, torch, Hn, B, synth):
+    """pool_set_split over the alpha grid: time of each move (call + device work), rows evicted / moved, and the
+    lookups that follow it (hit rate, time per batch including the miss path)."""
+    dev = Hn.DEV
+    d, pt, L = c["d"], c["pt"], c["L"]
+    rows = c["rows"]
+    import gc
+    gc.collect()
+    table = None
+    while table is None:
+        try:
+            table = torch.empty((rows, d), dtype=torch.int16, pin_memory=True)
+        except RuntimeError:
+            rows //= 2  # the host cannot pin that much: halve the table (said in the output)
+    synth.fill_table_bf16_torch(table, synth.SEED_BASE + c["index"], dev)
+    torch.cuda.synchronize()
+    page_size = pt * 2 * L * d * 2
+    n_pages = c["pool_bytes"] // page_size
+    pool = Hn.Pool(n_pages, page_size, d * 2, B.ELEM_BF16, pt, 32, table.view(torch.bfloat16), c["alpha"], zero_fill=False)
+    rng = synth.rng_for(c["index"], 5)
+    lens = synth.history_lengths(rng, c["batch"], c["mean_len"], c["min_len"], c["max_len"])
+    tokens = int(lens.sum())
+    out = torch.empty((tokens, d), dtype=torch.bfloat16, device=dev)
+    # warm: one sweep over the table (the cache at 0.8 holds more slots than the table has rows)
+    for lo in range(0, rows, tokens):
+        sweep = torch.arange(lo, lo + tokens, dtype=torch.int64, device=dev) % rows
+        assert B.emb_lookup(pool.h, sweep, out, 1, None) == B.OK, B.last_error()
+    torch.cuda.synchronize()
+    R = d * 2
+    grid = [round(0.8 - 0.05 * k, 2) for k in range(1, 13)] + [round(0.2 + 0.05 * k, 2) for k in range(1, 13)]
+    steps = []
+    for alpha in grid:
+        st0 = pool.stats()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rc, ach = B.pool_set_split(pool.h, alpha)
+        t1 = time.perf_counter()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        assert rc in (B.OK, B.DEFERRED), (rc, B.last_error())
+        st1 = pool.stats()
+        lk = []
+        for k in range(args.steps):
+            ids = torch.from_numpy(synth.zipf_ids(rng, rows, c["zipf"], tokens)).to(dev)
+            torch.cuda.synchronize()
+            ta = time.perf_counter()
+            assert B.emb_lookup(pool.h, ids, out, 1, None) == B.OK, B.last_error()
+            torch.cuda.synchronize()
+            lk.append(time.perf_counter() - ta)
+        st2 = pool.stats()
+        lookups = st2["lookups"] - st1["lookups"]
+        moved, evicted = st1["shrink_moved"] - st0["shrink_moved"], st1["shrink_evicted"] - st0["shrink_evicted"]
+        steps.append({"alpha": alpha, "achieved": ach, "pages_moved": abs(int(st1["pages_emb"]) - int(st0["pages_emb"])),
+                      "host_ms": (t1 - t0) * 1e3, "total_ms": (t2 - t0) * 1e3, "rows_evicted": int(evicted),
+                      "rows_moved": int(moved), "moved_MB": 2 * R * moved / 1e6,
+                      "hit_rate": (st2["hits"] - st1["hits"]) / max(lookups, 1),
+                      "miss_MB_per_batch": (st2["unique_misses"] - st1["unique_misses"]) * R / 1e6 / args.steps,
+                      "lookup_ms": 1e3 * sum(lk) / len(lk)})
+    down = [s_ for s_ in steps[:12]]
+    print(json.dumps({
+        "metric": "pool_set_split_ms", "value": sum(s_["total_ms"] for s_ in down) / len(down), "unit": "ms per 0.05 shrink",
+        "n_gpus": 1, "steps": args.steps, "warmup": 0, "ms_per_step": sum(s_["total_ms"] for s_ in down) / len(down),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": c["desc"], "table_rows": rows, "pages": int(n_pages), "lookups_per_batch": tokens},
+        "moves": steps}))
+    pool.close()
+
+
 def one_step(wl, k, B):
     ids = wl["ids_dev"][k % len(wl["ids_dev"])]
     rc = B.emb_lookup(wl["pool"].h, ids, wl["x"], 1, None)
@@ -317,6 +391,9 @@ def main():
         return
     if c.get("attn_only"):
         attn_only_bench(args, c, torch, Hn, B, synth)
+        return
+    if c.get("split_sweep"):
+        split_sweep_bench(args, c, torch, Hn, B, synth)
         return
     wl = build_workload(c, torch, Hn, B, synth)
     pool = wl["pool"]

@@ -703,9 +703,13 @@ __global__ __launch_bounds__(256) void emb_shrink_sets(EmbView v, uint32_t old_f
     const uint32_t a = act ? old_full + (s < old_part_sets ? 1u : 0u) : 0;
     const uint32_t b = act ? ways_of(v, s) : 0;
     const bool shrinks = b < a;
+    // A set whose removed ways hold nothing keeps all its entries where they are: most sets of a cache that is
+    // not full.  Only the removed ways' tags are read to find that out (a few bytes of the set's tag line).
     uint32_t tg = kEmpty, sp = 0;
+    if (shrinks && l32 >= b && l32 < a) tg = v.tags[static_cast<uint64_t>(s) * v.w_max + l32];
+    if (__ballot(tg != kEmpty) == 0) continue;
     if (shrinks && l32 < a) {
-      tg = v.tags[static_cast<uint64_t>(s) * v.w_max + l32];
+      if (l32 < b) tg = v.tags[static_cast<uint64_t>(s) * v.w_max + l32];
       sp = v.stamps[static_cast<uint64_t>(s) * v.w_max + l32];
     }
     const bool live = tg != kEmpty;
@@ -834,9 +838,11 @@ hipError_t launch_emb_miss_path(const EmbView& v, const MissWs& ws, const int64_
 }
 
 hipError_t launch_emb_shrink(const EmbView& v, uint32_t old_full, uint32_t old_part_sets, hipStream_t stream) {
+  // one pass over the sets with as many blocks as that takes: each set costs one dependent round trip to
+  // memory, so the latency is hidden by the number of wavefronts in flight, not by a loop
   const uint32_t waves_needed = (v.sets + 1) / 2;
   uint32_t blocks = (waves_needed + 3) / 4;
-  if (blocks > 8192) blocks = 8192;
+  if (blocks > (1u << 20)) blocks = 1u << 20;
   if (blocks == 0) blocks = 1;
   hipLaunchKernelGGL(emb_shrink_sets, dim3(blocks), dim3(256), 0, stream, v, old_full, old_part_sets);
   return hipGetLastError();
