@@ -528,6 +528,13 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
 
     }
   }
+  // The LayerNorm parameters are done with; their LDS space takes this block's slice of the bias (at most
+  // 2 KD columns per block).  Nothing inside the sweep below may read global memory for immediate use: the
+  // wait for such a load also waits for every store and every weight prefetch issued before it.
+  const uint32_t cb0 = blockIdx.y * a.col_blocks_per_split, n_cb = a.col_blocks_per_split;
+  float* bias_s = &lnp[0][0];
+  __syncthreads();
+  for (uint32_t i = tid; i < n_cb * 32; i += 64 * WPB) bias_s[i] = a.bias[cb0 * 32 + i];
 
   // ---- where this lane's token goes ---------------------------------------------------------
   const uint8_t* page_ptr = nullptr;  // FRONT: start of the token's page (nullptr: bad page id)
@@ -605,14 +612,29 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
 #pragma unroll
   for (uint32_t j = 0; j < 4; ++j) swz[j] = li * KD + 8 * ((2 * j + g) ^ (li & 7));
 
+  // BACK: the residual pieces a lane adds at its two stores, fetched one tile ahead (the wait for them then
+  // covers the stores of the tile before, not those just issued)
+  struct RSet { uint4 r0, r1; };
+  // (row2 of a lane without a row points at the tile's first row, so the loads need no condition)
+  auto fetch_resid = [&](RSet& rs, uint32_t cb) {
+    if (FRONT) return;
+    rs.r0 = *reinterpret_cast<const uint4*>(a.resid + row2[0] * KD + cb * 32 + 8 * (lane & 3));
+    rs.r1 = *reinterpret_cast<const uint4*>(a.resid + row2[1] * KD + cb * 32 + 8 * (lane & 3));
+  };
+
+  // Prefetches are issued unconditionally (past the end they fetch the last tile again): the compiler sizes
+  // each wait by the memory operations that every path issues after the awaited one, and a prefetch under a
+  // condition would make it wait for the stores just issued as well.
+  const uint32_t cb_last = cb0 + n_cb - 1;
   // one 32-column tile: product, epilogue, stores
-  auto compute = [&](const uint16_t* wb, uint32_t cb) {
+  auto compute = [&](const uint16_t* wb, uint32_t cb, const RSet& res, RSet& res_next) {
     const uint32_t n0 = cb * 32;
+    fetch_resid(res_next, cb < cb_last ? cb + 1 : cb_last);
     f32x16 acc;
     // acc[e]: feature n0 + 8*(e/4) + 4*g + e%4 of this lane's token; the bias is the starting value
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
-      const float4 b = *reinterpret_cast<const float4*>(a.bias + n0 + 8 * r4 + 4 * g);
+      const float4 b = *reinterpret_cast<const float4*>(bias_s + (cb - cb0) * 32 + 8 * r4 + 4 * g);
       acc[4 * r4] = b.x; acc[4 * r4 + 1] = b.y; acc[4 * r4 + 2] = b.z; acc[4 * r4 + 3] = b.w;
     }
 #pragma unroll
@@ -665,33 +687,33 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
         if (!ok2[h2]) continue;
         const uint64_t at = row2[h2] * KD + n0 + 8 * (lane & 3);
         float xv[8];
-        unpack8(*reinterpret_cast<const uint4*>(a.resid + at), xv);
+        unpack8(h2 == 0 ? res.r0 : res.r1, xv);
         *reinterpret_cast<uint4*>(a.y + at) = make_uint4(pack2_bf16(xv[0] + p0.x, xv[1] + p0.y), pack2_bf16(xv[2] + p0.z, xv[3] + p0.w),
                                                         pack2_bf16(xv[4] + p1.x, xv[5] + p1.y), pack2_bf16(xv[6] + p1.z, xv[7] + p1.w));
       }
     }
   };
 
-  const uint32_t cb0 = blockIdx.y * a.col_blocks_per_split, n_cb = a.col_blocks_per_split;
+  RSet resA{zero4, zero4}, resB{zero4, zero4};
+  auto tile_at = [&](uint32_t k) { return cb0 + k < cb_last ? cb0 + k : cb_last; };
+  fetch_resid(resA, cb0);
   fetch_w(wregA, cb0);
-  if (n_cb > 1) fetch_w(wregB, cb0 + 1);
+  fetch_w(wregB, tile_at(1));
+  asm volatile("" ::: "memory");  // keeps the issue order: the waits inside the loop are sized by it
   commit_w(wregA, wtile[0]);
-  if (n_cb > 2) fetch_w(wregA, cb0 + 2);
-  for (uint32_t k = 0; k < n_cb; k += 2) {
+  asm volatile("" ::: "memory");
+  fetch_w(wregA, tile_at(2));
+  asm volatile("" ::: "memory");
+  for (uint32_t k = 0; k < n_cb; k += 2) {  // n_cb is even (the launchers check it)
     // tile k is visible, and every wave is done with tile k-1, whose buffer takes tile k+1
     __syncthreads();
-    if (k + 1 < n_cb) {
-      commit_w(wregB, wtile[1]);
-      if (k + 3 < n_cb) fetch_w(wregB, cb0 + k + 3);
-    }
-    compute(wtile[0], cb0 + k);
-    if (k + 1 >= n_cb) break;
+    commit_w(wregB, wtile[1]);
+    fetch_w(wregB, tile_at(k + 3));
+    compute(wtile[0], cb0 + k, resA, resB);
     __syncthreads();
-    if (k + 2 < n_cb) {
-      commit_w(wregA, wtile[0]);
-      if (k + 4 < n_cb) fetch_w(wregA, cb0 + k + 4);
-    }
-    compute(wtile[1], cb0 + k + 1);
+    commit_w(wregA, wtile[0]);  // after the last pair: a copy of the last tile that nobody reads
+    fetch_w(wregA, tile_at(k + 4));
+    compute(wtile[1], cb0 + k + 1, resB, resA);
   }
 }
 
@@ -1337,6 +1359,7 @@ hipError_t launch_layer_front_fused(const HstuDims& hd, uint32_t layer, const vo
   a.row_tiles = sl.row_tiles;
   constexpr uint32_t kSplit = 2;  // column halves: U|V and Q|K
   a.col_blocks_per_split = 4 * hd.d / 32 / kSplit;
+  if (a.col_blocks_per_split % 2 != 0) return hipErrorInvalidValue;  // the sweep takes column tiles in pairs
   const dim3 grid(sl.n_row_tiles, kSplit), block(256);
   if (hd.d == 256) hipLaunchKernelGGL((layer_half_fused<256, true, 4>), grid, block, 0, stream, a);
   else hipLaunchKernelGGL((layer_half_fused<128, true, 4>), grid, block, 0, stream, a);
@@ -1360,6 +1383,7 @@ hipError_t launch_layer_back_fused(const HstuDims& hd, const void* o, const void
   a.y = static_cast<uint16_t*>(y);
   a.row_tiles = sl.row_tiles;
   a.col_blocks_per_split = hd.d / 32;
+  if (a.col_blocks_per_split % 2 != 0) return hipErrorInvalidValue;  // the sweep takes column tiles in pairs
   const dim3 grid(sl.n_row_tiles, 1), block(256);
   if (hd.d == 256) hipLaunchKernelGGL((layer_half_fused<256, false, 4>), grid, block, 0, stream, a);
   else hipLaunchKernelGGL((layer_half_fused<128, false, 4>), grid, block, 0, stream, a);
