@@ -460,27 +460,88 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
   const uint64_t row = rt.row0 + (row_ok ? rloc : 0);
   const HstuDims& hd = a.hd;
 
+  // ---- where this lane's token goes (looked up first: the dependent loads fly during the LayerNorm) ----
+  const uint8_t* page_ptr = nullptr;  // FRONT: start of the token's page (nullptr: bad page id)
+  uint32_t tok = 0;
+  if (FRONT) {
+    const ReqDev rq = a.reqs[rt.req];
+    const uint32_t pos = rq.prefix_len + static_cast<uint32_t>(row - rq.x_off);
+    uint32_t pi;
+    split_token(hd, pos, &pi, &tok);
+    if (row_ok) {
+      const int32_t page = a.page_tables[rq.page_table_off + pi];
+      if (page < 0 || static_cast<uint32_t>(page) >= a.kv.n_pages) {
+        if (blockIdx.y == 0 && g == 0) atomicAdd(&a.kv.counters[ctr_index(kCtrBadPages)], 1ull);
+      } else {
+        page_ptr = a.kv.base + static_cast<uint64_t>(page) * a.kv.page_size;
+      }
+    }
+  }
+
+  // Row-major outputs leave through a wave-private LDS tile that turns "one token, four runs of four
+  // features per lane" into 16-byte pieces: lane l then stores features 8 (l % 4) .. + 8 of the tokens
+  // l / 4 and l / 4 + 16 of its wavefront, so four lanes cover 64 contiguous bytes of a row.
+  const bool wave_has_rows = 32 * (WPB * sub + wave) < rt.rows;
+  bool ok2[2];
+  uint64_t row2[2];
+  uint8_t* kdst2[2] = {nullptr, nullptr};  // FRONT: K row of the token inside its page, before the head offset
+#pragma unroll
+  for (int h2 = 0; h2 < 2; ++h2) {
+    const uint32_t rl = 32 * (WPB * sub + wave) + (lane >> 2) + 16 * h2;
+    ok2[h2] = rl < rt.rows;
+    row2[h2] = rt.row0 + (ok2[h2] ? rl : 0);
+    if (FRONT && ok2[h2]) {
+      const ReqDev rq = a.reqs[rt.req];
+      const uint32_t pos = rq.prefix_len + static_cast<uint32_t>(row2[h2] - rq.x_off);
+      uint32_t pi, tk;
+      split_token(hd, pos, &pi, &tk);
+      const int32_t page = a.page_tables[rq.page_table_off + pi];
+      if (page >= 0 && static_cast<uint32_t>(page) < a.kv.n_pages)
+        kdst2[h2] = a.kv.base + static_cast<uint64_t>(page) * a.kv.page_size + static_cast<uint64_t>(tk) * 128;
+    }
+  }
   // ---- activations: load, normalise, keep as MFMA operand ----------------------------------
   __shared__ __attribute__((aligned(16))) float lnp[2][KD];  // LayerNorm scale and shift
   for (uint32_t i = tid; i < KD; i += 64 * WPB) {
     lnp[0][i] = a.ln_g[i];
     lnp[1][i] = a.ln_b[i];
   }
-  uint4 xr[kSt];  // this lane's half of its token's row: raw, then normalised (and gated) bf16
+  // A wavefront's 32 rows come in with whole-line loads (a load instruction covers the same half of 64 / (KD/16)
+  // rows, 16 bytes per lane) and are dealt out to the operand layout (lane = token, 8 of every 16 elements)
+  // through LDS: half a row of each of the 32 rows at a time, in the wavefront's quarter of the weight tile
+  // buffers, which nothing uses before the first barrier below.  Chunk c of row r sits at c ^ (r mod chunks).
+  // Rows past the tile's end read its first row; their results are never stored.
+  constexpr int kHalfChunks = KD / 16;            // 16-byte chunks in half a row
+  constexpr int kRowsPerLoad = 64 / kHalfChunks;  // rows one wave-wide load covers
+  constexpr int kLoads = 32 / kRowsPerLoad;       // loads per half
+  static_assert(kSt % 2 == 0 && 64 % kHalfChunks == 0 && 32 % kRowsPerLoad == 0, "row staging layout");
+  auto load_rows = [&](const uint16_t* src, uint4 (&dst)[kSt]) {
+    uint16_t* stage = &wtile[0][0] + wave * (32 * KD / 2);
+    const uint32_t lr = lane / kHalfChunks, lc = lane % kHalfChunks;
 #pragma unroll
-  for (int st = 0; st < kSt; ++st) {
-    xr[st] = make_uint4(0, 0, 0, 0);
-    if (row_ok) xr[st] = *reinterpret_cast<const uint4*>(a.a_in + row * KD + 16 * st + 8 * g);
-  }
+    for (int h = 0; h < 2; ++h) {
+      uint4 v[kLoads];
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) {
+        const uint32_t rl = 32 * (WPB * sub + wave) + kRowsPerLoad * i + lr;
+        v[i] = *reinterpret_cast<const uint4*>(src + (rt.row0 + (rl < rt.rows ? rl : 0)) * KD + 8 * (kHalfChunks * h + lc));
+      }
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) {
+        const uint32_t r = kRowsPerLoad * i + lr;
+        *reinterpret_cast<uint4*>(stage + r * (KD / 2) + 8 * (lc ^ (r & (kHalfChunks - 1)))) = v[i];
+      }
+#pragma unroll
+      for (int s2 = 0; s2 < kSt / 2; ++s2)
+        dst[kSt / 2 * h + s2] =
+            *reinterpret_cast<const uint4*>(stage + li * (KD / 2) + 8 * ((2 * s2 + g) ^ (li & (kHalfChunks - 1))));
+    }
+  };
+  uint4 xr[kSt];  // this lane's half of its token's row: raw, then normalised (and gated) bf16
+  load_rows(a.a_in, xr);
   {
     uint4 gr[FRONT ? 1 : kSt];  // BACK: the gate row
-    if (!FRONT) {
-#pragma unroll
-      for (int st = 0; st < kSt; ++st) {
-        gr[st] = make_uint4(0, 0, 0, 0);
-        if (row_ok) gr[st] = *reinterpret_cast<const uint4*>(a.gate + row * KD + 16 * st + 8 * g);
-      }
-    }
+    if constexpr (!FRONT) load_rows(a.gate, gr);
     float s = 0.0f;
 #pragma unroll
     for (int st = 0; st < kSt; ++st) {
@@ -536,46 +597,6 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
   __syncthreads();
   for (uint32_t i = tid; i < n_cb * 32; i += 64 * WPB) bias_s[i] = a.bias[cb0 * 32 + i];
 
-  // ---- where this lane's token goes ---------------------------------------------------------
-  const uint8_t* page_ptr = nullptr;  // FRONT: start of the token's page (nullptr: bad page id)
-  uint32_t tok = 0;
-  if (FRONT) {
-    const ReqDev rq = a.reqs[rt.req];
-    const uint32_t pos = rq.prefix_len + static_cast<uint32_t>(row - rq.x_off);
-    uint32_t pi;
-    split_token(hd, pos, &pi, &tok);
-    if (row_ok) {
-      const int32_t page = a.page_tables[rq.page_table_off + pi];
-      if (page < 0 || static_cast<uint32_t>(page) >= a.kv.n_pages) {
-        if (blockIdx.y == 0 && g == 0) atomicAdd(&a.kv.counters[ctr_index(kCtrBadPages)], 1ull);
-      } else {
-        page_ptr = a.kv.base + static_cast<uint64_t>(page) * a.kv.page_size;
-      }
-    }
-  }
-
-  // Row-major outputs leave through a wave-private LDS tile that turns "one token, four runs of four
-  // features per lane" into 16-byte pieces: lane l then stores features 8 (l % 4) .. + 8 of the tokens
-  // l / 4 and l / 4 + 16 of its wavefront, so four lanes cover 64 contiguous bytes of a row.
-  const bool wave_has_rows = 32 * (WPB * sub + wave) < rt.rows;
-  bool ok2[2];
-  uint64_t row2[2];
-  uint8_t* kdst2[2] = {nullptr, nullptr};  // FRONT: K row of the token inside its page, before the head offset
-#pragma unroll
-  for (int h2 = 0; h2 < 2; ++h2) {
-    const uint32_t rl = 32 * (WPB * sub + wave) + (lane >> 2) + 16 * h2;
-    ok2[h2] = rl < rt.rows;
-    row2[h2] = rt.row0 + (ok2[h2] ? rl : 0);
-    if (FRONT && ok2[h2]) {
-      const ReqDev rq = a.reqs[rt.req];
-      const uint32_t pos = rq.prefix_len + static_cast<uint32_t>(row2[h2] - rq.x_off);
-      uint32_t pi, tk;
-      split_token(hd, pos, &pi, &tk);
-      const int32_t page = a.page_tables[rq.page_table_off + pi];
-      if (page >= 0 && static_cast<uint32_t>(page) < a.kv.n_pages)
-        kdst2[h2] = a.kv.base + static_cast<uint64_t>(page) * a.kv.page_size + static_cast<uint64_t>(tk) * 128;
-    }
-  }
   constexpr int kOutStride = FRONT ? 40 : 72;  // 16-bit units per token row of the tile: 32 bf16 or 32 fp32, padded
   __shared__ __attribute__((aligned(16))) uint16_t otile[WPB][32 * kOutStride];
   uint16_t* ot = otile[wave];
