@@ -460,7 +460,46 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
   const uint64_t row = rt.row0 + (row_ok ? rloc : 0);
   const HstuDims& hd = a.hd;
 
-  // ---- where this lane's token goes (looked up first: the dependent loads fly during the LayerNorm) ----
+  // ---- activation rows: issue the loads ---------------------------------------------------------
+  // A wavefront's 32 rows come in with whole-line loads (a load instruction covers the same half of 64 / (KD/16)
+  // rows, 16 bytes per lane) and are dealt out to the operand layout (lane = token, 8 of every 16 elements)
+  // through LDS: half a row of each of the 32 rows at a time, in the wavefront's quarter of the weight tile
+  // buffers, which nothing uses before the first barrier below.  Chunk c of row r sits at c ^ (r mod chunks).
+  // Rows past the tile's end read its first row; their results are never stored.
+  constexpr int kHalfChunks = KD / 16;            // 16-byte chunks in half a row
+  constexpr int kRowsPerLoad = 64 / kHalfChunks;  // rows one wave-wide load covers
+  constexpr int kLoads = 32 / kRowsPerLoad;       // loads per half
+  static_assert(kSt % 2 == 0 && 64 % kHalfChunks == 0 && 32 % kRowsPerLoad == 0, "row staging layout");
+  const uint32_t stage_lr = lane / kHalfChunks, stage_lc = lane % kHalfChunks;
+  auto issue_rows = [&](const uint16_t* src, int h, uint4 (&v)[kLoads]) {
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+      const uint32_t rl = 32 * (WPB * sub + wave) + kRowsPerLoad * i + stage_lr;
+      v[i] = *reinterpret_cast<const uint4*>(src + (rt.row0 + (rl < rt.rows ? rl : 0)) * KD + 8 * (kHalfChunks * h + stage_lc));
+    }
+  };
+  auto deal_rows = [&](const uint4 (&v)[kLoads], int h, uint4 (&dst)[kSt]) {
+    uint16_t* stage = &wtile[0][0] + wave * (32 * KD / 2);
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+      const uint32_t r = kRowsPerLoad * i + stage_lr;
+      *reinterpret_cast<uint4*>(stage + r * (KD / 2) + 8 * (stage_lc ^ (r & (kHalfChunks - 1)))) = v[i];
+    }
+#pragma unroll
+    for (int s2 = 0; s2 < kSt / 2; ++s2)
+      dst[kSt / 2 * h + s2] =
+          *reinterpret_cast<const uint4*>(stage + li * (KD / 2) + 8 * ((2 * s2 + g) ^ (li & (kHalfChunks - 1))));
+  };
+  uint4 va[kLoads], vb[kLoads];
+  issue_rows(a.a_in, 0, va);
+  issue_rows(a.a_in, 1, vb);
+  uint4 xr[kSt];  // this lane's half of its token's row: raw, then normalised (and gated) bf16
+  deal_rows(va, 0, xr);
+  if constexpr (!FRONT) issue_rows(a.gate, 0, va);
+  deal_rows(vb, 1, xr);
+  if constexpr (!FRONT) issue_rows(a.gate, 1, vb);
+
+  // ---- where this lane's token goes (these dependent loads fly during the LayerNorm) ----------------
   const uint8_t* page_ptr = nullptr;  // FRONT: start of the token's page (nullptr: bad page id)
   uint32_t tok = 0;
   if (FRONT) {
@@ -506,42 +545,12 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
     lnp[0][i] = a.ln_g[i];
     lnp[1][i] = a.ln_b[i];
   }
-  // A wavefront's 32 rows come in with whole-line loads (a load instruction covers the same half of 64 / (KD/16)
-  // rows, 16 bytes per lane) and are dealt out to the operand layout (lane = token, 8 of every 16 elements)
-  // through LDS: half a row of each of the 32 rows at a time, in the wavefront's quarter of the weight tile
-  // buffers, which nothing uses before the first barrier below.  Chunk c of row r sits at c ^ (r mod chunks).
-  // Rows past the tile's end read its first row; their results are never stored.
-  constexpr int kHalfChunks = KD / 16;            // 16-byte chunks in half a row
-  constexpr int kRowsPerLoad = 64 / kHalfChunks;  // rows one wave-wide load covers
-  constexpr int kLoads = 32 / kRowsPerLoad;       // loads per half
-  static_assert(kSt % 2 == 0 && 64 % kHalfChunks == 0 && 32 % kRowsPerLoad == 0, "row staging layout");
-  auto load_rows = [&](const uint16_t* src, uint4 (&dst)[kSt]) {
-    uint16_t* stage = &wtile[0][0] + wave * (32 * KD / 2);
-    const uint32_t lr = lane / kHalfChunks, lc = lane % kHalfChunks;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      uint4 v[kLoads];
-#pragma unroll
-      for (int i = 0; i < kLoads; ++i) {
-        const uint32_t rl = 32 * (WPB * sub + wave) + kRowsPerLoad * i + lr;
-        v[i] = *reinterpret_cast<const uint4*>(src + (rt.row0 + (rl < rt.rows ? rl : 0)) * KD + 8 * (kHalfChunks * h + lc));
-      }
-#pragma unroll
-      for (int i = 0; i < kLoads; ++i) {
-        const uint32_t r = kRowsPerLoad * i + lr;
-        *reinterpret_cast<uint4*>(stage + r * (KD / 2) + 8 * (lc ^ (r & (kHalfChunks - 1)))) = v[i];
-      }
-#pragma unroll
-      for (int s2 = 0; s2 < kSt / 2; ++s2)
-        dst[kSt / 2 * h + s2] =
-            *reinterpret_cast<const uint4*>(stage + li * (KD / 2) + 8 * ((2 * s2 + g) ^ (li & (kHalfChunks - 1))));
-    }
-  };
-  uint4 xr[kSt];  // this lane's half of its token's row: raw, then normalised (and gated) bf16
-  load_rows(a.a_in, xr);
   {
     uint4 gr[FRONT ? 1 : kSt];  // BACK: the gate row
-    if constexpr (!FRONT) load_rows(a.gate, gr);
+    if constexpr (!FRONT) {
+      deal_rows(va, 0, gr);
+      deal_rows(vb, 1, gr);
+    }
     float s = 0.0f;
 #pragma unroll
     for (int st = 0; st < kSt; ++st) {
