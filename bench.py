@@ -48,6 +48,16 @@ CONFIGS = {
                   batch=128, mean_len=3072, min_len=512, max_len=12288, zipf=0.9, n_time=32, split_sweep=True,
                   desc="Split sweep: 128 GiB pool, table 100Mx256 bf16 pinned host, EMB:KV 0.8 -> 0.2 -> 0.8 in steps of "
                        "0.05 with page remap/eviction, batches of 128 lognormal(512..12k) histories, Zipf(0.9) ids"),
+    # Serving loop with KV reuse at every split of the grid: a request of a user whose history is still cached
+    # computes its 64 newest tokens only, any other recomputes the whole history; lookups that miss the hot cache
+    # go to the host table.  Half the size of the split-sweep configuration (pool, table and users scaled alike).
+    "alphacurve": dict(index=5, L=4, d=256, H=4, bf16=True, rows=50_000_000, pool_bytes=64 << 30, pt=64, alpha=0.8,
+                       batch=128, mean_len=3072, min_len=512, max_len=12288, zipf=0.9, n_time=32, alpha_curve=True,
+                       users=8192, user_zipf=0.6, new=64, bag=8,
+                       desc="Serving loop over the split grid 0.8 -> 0.2: 64 GiB pool, table 50Mx256 bf16 pinned host, "
+                            "8192 users (Zipf 0.6 popularity, lognormal 512..12k histories), batches of 128 requests, "
+                            "64 new tokens on a KV hit, full recompute otherwise, 8 sum-pooled features per token "
+                            "(disjoint row ranges, Zipf(0.9) each)"),
     "tiny": dict(index=0, L=1, d=64, H=2, bf16=False, rows=100_000, pool_bytes=4 << 20, pt=16, alpha=0.5,
                  batch=4, mean_len=256, min_len=256, max_len=256, zipf=1.0, n_time=32, warm_batches=4,
                  desc="Tiny: 1 layer d=64 H=2 fp32, table 100k x 64 fp32, 4 MiB pool, 4 x 256 tokens, KV page 16"),
@@ -313,6 +323,120 @@ def split_sweep_bench(args, c, torch, Hn, B, synth):
     pool.close()
 
 
+def alpha_curve_bench(args, c, torch, Hn, B, synth):
+    """Step time of a serving loop against the EMB:KV split (the trade-off of the paper's Sec. III, Fig. 4): the
+    embedding side gets slower as the hot cache shrinks (misses cross PCIe), the attention side gets slower as
+    the KV share shrinks (fewer users stay cached, their histories are recomputed).  One curve per mean history
+    length; per split: KV hit rate, cache hit rate, miss bytes, time of emb_lookup and of hstu_step."""
+    dev = Hn.DEV
+    L, d, H, pt = c["L"], c["d"], c["H"], c["pt"]
+    rows = c["rows"]
+    table = None
+    while table is None:
+        try:
+            table = torch.empty((rows, d), dtype=torch.int16, pin_memory=True)
+        except RuntimeError:
+            rows //= 2  # the host cannot pin that much: halve the table (said in the output)
+    synth.fill_table_bf16_torch(table, synth.SEED_BASE + c["index"], dev)
+    torch.cuda.synchronize()
+    page_size = pt * 2 * L * d * 2
+    n_pages = c["pool_bytes"] // page_size
+    n_pos = c["max_len"]
+    rng = synth.rng_for(c["index"])
+    w = synth.make_weights(rng, L, d, H, n_pos, c["n_time"], True)
+    model = Hn.Model(L, d, H, B.ELEM_BF16, pt, n_pos, c["n_time"], float(n_pos), w)
+    ts_all = synth.timestamps(rng, c["max_len"])
+    users, new = c["users"], c["new"]
+    pop = np.arange(1, users + 1, dtype=np.float64) ** (-c["user_zipf"])
+    pop /= pop.sum()
+    grid = [round(0.8 - 0.05 * k, 2) for k in range(13)]
+    curves = []
+    for mean_len in (c["mean_len"] * 2 // 3, c["mean_len"] * 4 // 3):
+        pool = Hn.Pool(n_pages, page_size, d * 2, B.ELEM_BF16, pt, 32, table.view(torch.bfloat16), c["alpha"],
+                       zero_fill=True)
+        lens = synth.history_lengths(rng, users, mean_len, c["min_len"], c["max_len"])
+        user_of_rank = rng.permutation(users)
+        sweep_n = 1 << 19
+        out_sweep = torch.empty((sweep_n, d), dtype=torch.bfloat16, device=dev)
+        # warm the hot cache: one pass over the table, then a Zipf stream that sets the LRU order
+        for lo in range(0, rows, sweep_n):
+            ids = torch.arange(lo, lo + sweep_n, dtype=torch.int64, device=dev) % rows
+            assert B.emb_lookup(pool.h, ids, out_sweep, 1, None) == B.OK, B.last_error()
+        for _ in range(40):
+            ids = torch.from_numpy(synth.multi_feature_ids(rng, rows, c["bag"], c["zipf"], sweep_n // c["bag"])).to(dev)
+            assert B.emb_lookup(pool.h, ids, out_sweep, 1, None) == B.OK, B.last_error()
+        torch.cuda.synchronize()
+
+        def serve(timed):
+            """One batch; returns (requests, KV hits, new tokens, emb s, hstu s)."""
+            picked = np.unique(user_of_rank[rng.choice(users, size=c["batch"], p=pop)])
+            prefix, newt, pages, keys = [], [], [], []
+            for u in picked:
+                S = int(lens[u])
+                rc, tok, _ = B.kv_seq_lookup(pool.h, int(u))
+                hit = rc == B.OK and tok >= S
+                rc, pg = B.kv_seq_reserve(pool.h, int(u), S)
+                if rc != B.OK:
+                    continue  # the KV side cannot hold this batch: the request is dropped (counted below)
+                B.kv_seq_pin(pool.h, int(u))
+                keys.append(int(u))
+                prefix.append(S - new if hit else 0)
+                newt.append(new if hit else S)
+                pages.append(pg[: (S + pt - 1) // pt])
+            reqs, n_pt, n_ts, N = synth.make_requests(prefix, newt, pt)
+            pts = torch.from_numpy(np.concatenate(pages).astype(np.int32)).to(dev)
+            ts = torch.from_numpy(np.concatenate([ts_all[: p_ + t_] for p_, t_ in zip(prefix, newt)])).to(dev)
+            ids = torch.from_numpy(synth.multi_feature_ids(rng, rows, c["bag"], c["zipf"], N)).to(dev)
+            x = torch.empty((N, d), dtype=torch.bfloat16, device=dev)
+            y = torch.empty((N, d), dtype=torch.bfloat16, device=dev)
+            reqs_c = (B.make_reqs(reqs), len(reqs))
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            rc = B.emb_lookup(pool.h, ids, x, c["bag"], None)
+            assert rc == B.OK, (rc, B.last_error())
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            rc = B.hstu_step(pool.h, model.h, reqs_c, pts, x, ts, y)
+            assert rc == B.OK, (rc, B.last_error())
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            for k_ in keys:
+                B.kv_seq_unpin(pool.h, k_)
+            hits = sum(1 for p_ in prefix if p_ > 0)
+            return len(picked), len(keys), hits, N, t1 - t0, t2 - t1
+
+        points = []
+        for alpha in grid:
+            rc, ach = B.pool_set_split(pool.h, alpha)
+            assert rc in (B.OK, B.DEFERRED), (rc, B.last_error())
+            for _ in range(args.warmup):
+                serve(False)
+            st0 = pool.stats()
+            acc = np.zeros(6)
+            for _ in range(args.steps):
+                acc += np.array(serve(True), dtype=np.float64)
+            st1 = pool.stats()
+            lookups = st1["lookups"] - st0["lookups"]
+            points.append({"alpha": alpha, "achieved": ach, "kv_hit_rate": acc[2] / max(acc[1], 1),
+                           "dropped_requests": int(acc[0] - acc[1]),
+                           "emb_hit_rate": (st1["hits"] - st0["hits"]) / max(lookups, 1),
+                           "miss_MB_per_step": (st1["unique_misses"] - st0["unique_misses"]) * d * 2 / 1e6 / args.steps,
+                           "new_tokens_per_step": acc[3] / args.steps, "emb_ms": 1e3 * acc[4] / args.steps,
+                           "hstu_ms": 1e3 * acc[5] / args.steps, "total_ms": 1e3 * (acc[4] + acc[5]) / args.steps})
+            print("alphacurve mean %d: %s" % (mean_len, json.dumps(points[-1])), file=sys.stderr, flush=True)
+        best = min(points, key=lambda q: q["total_ms"])
+        curves.append({"mean_history": int(mean_len), "best_alpha": best["alpha"], "best_total_ms": best["total_ms"],
+                       "points": points})
+        pool.close()
+        del pool, out_sweep
+    print(json.dumps({
+        "metric": "serving_step_ms_at_best_split", "value": curves[0]["best_total_ms"], "unit": "ms per batch of %d requests" % c["batch"],
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": curves[0]["best_total_ms"],
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": c["desc"], "table_rows": rows, "pages": int(n_pages)}, "curves": curves}))
+    model.close()
+
+
 def one_step(wl, k, B):
     ids = wl["ids_dev"][k % len(wl["ids_dev"])]
     rc = B.emb_lookup(wl["pool"].h, ids, wl["x"], 1, None)
@@ -394,6 +518,9 @@ def main():
         return
     if c.get("split_sweep"):
         split_sweep_bench(args, c, torch, Hn, B, synth)
+        return
+    if c.get("alpha_curve"):
+        alpha_curve_bench(args, c, torch, Hn, B, synth)
         return
     wl = build_workload(c, torch, Hn, B, synth)
     pool = wl["pool"]
