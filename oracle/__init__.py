@@ -87,6 +87,8 @@ def lib():
         L.orc_emb_set_of.argtypes = [vp, C.c_int64]
         L.orc_emb_set_of.restype = u64
         L.orc_emb_lookup.argtypes = [vp, vp, u64, u32, vp, u64, u32, i32, vp, vp]
+        L.orc_emb_refill.argtypes = [vp, vp, u64, u64, vp]
+        L.orc_emb_refill.restype = i32
         L.orc_round_bf16.argtypes = [C.c_float]
         L.orc_round_bf16.restype = C.c_float
         L.orc_f32_to_bf16_bits.argtypes = [C.c_float]
@@ -216,6 +218,13 @@ class Pool:
         hit = np.zeros(n, dtype=np.uint8)
         rc = lib().orc_emb_lookup(self._h, _ptr(ids), n, bag, _ptr(table), rows, d, elem, _ptr(out), _ptr(hit))
         return rc, out, hit
+
+    def emb_refill(self, ids, rows):
+        """Fill empty ways with `ids` (hottest first). Returns (rc, rows inserted)."""
+        ids = _c(ids, np.int64)
+        ins = C.c_uint64(0)
+        rc = lib().orc_emb_refill(self._h, _ptr(ids), ids.size, rows, C.byref(ins))
+        return rc, int(ins.value)
 
 
 def round_bf16(a):

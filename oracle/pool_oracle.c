@@ -468,3 +468,35 @@ int orc_emb_lookup(orc_pool* p, const int64_t* ids, uint64_t n, uint32_t bag, co
   free(is_hit);
   return ORC_OK;
 }
+
+/* Background refill of empty capacity (paper Sec. IV-B: after the EMB side has grown, the new
+ * space is filled with hot rows in the background).  `ids` comes in order of decreasing
+ * hotness.  The call is one batch of its own in LRU time.  A valid id that is not resident is
+ * put, once, into the lowest empty way of its set and stamped with the batch; a refill never
+ * evicts (an id whose set has no empty way is skipped), never touches the stamp of a resident
+ * row, and counts only in `inserted`.  Taken one id after the other, which is the same as "the
+ * k-th new id of a set takes its k-th empty way". */
+int orc_emb_refill(orc_pool* p, const int64_t* ids, uint64_t n, uint64_t rows, uint64_t* inserted) {
+  if (rows >= 0xFFFFFFFFull) return ORC_EINVAL;
+  p->t += 1;
+  const uint32_t t = p->t;
+  uint64_t ins = 0;
+  for (uint64_t i = 0; i < n; ++i) {
+    if (ids[i] < 0 || (uint64_t)ids[i] >= rows) continue;
+    uint64_t s = orc_emb_set_of(p, ids[i]);
+    uint32_t nw = ways_at(p, p->n_emb, s);
+    uint32_t* tg = p->tag + s * p->w_max;
+    int resident = 0, empty = -1;
+    for (uint32_t w = 0; w < nw; ++w) {
+      if (tg[w] == (uint32_t)ids[i]) resident = 1;
+      if (tg[w] == ORC_TAG_EMPTY && empty < 0) empty = (int)w;
+    }
+    if (resident || empty < 0) continue;
+    tg[empty] = (uint32_t)ids[i];
+    p->stamp[s * p->w_max + (uint32_t)empty] = t;
+    p->st.inserted++;
+    ins++;
+  }
+  if (inserted) *inserted = ins;
+  return ORC_OK;
+}

@@ -83,6 +83,8 @@ int orc_kv_seq_release(orc_pool* p, uint64_t key);
 uint64_t orc_emb_set_of(const orc_pool* p, int64_t id);
 int orc_emb_lookup(orc_pool* p, const int64_t* ids, uint64_t n, uint32_t bag, const void* table,
                    uint64_t rows, uint32_t d, int elem, void* out, uint8_t* hit);
+/* refill of empty ways with the given ids (hottest first); never evicts; *inserted may be NULL */
+int orc_emb_refill(orc_pool* p, const int64_t* ids, uint64_t n, uint64_t rows, uint64_t* inserted);
 
 /* ---- HSTU ---------------------------------------------------------------
  * All tensors are passed as fp32 arrays whose values are already representable

@@ -421,3 +421,82 @@ def test_zipf_hit_rate_is_in_the_harmonic_ballpark():
     rate = (s1["hits"] - s0["hits"]) / (s1["lookups"] - s0["lookups"])
     h = lambda n: np.log(n) + 0.5772
     assert 0.6 * h(C) / h(N) < rate < 1.15 * h(C) / h(N)
+
+
+# --------------------------------------------------------------------------- refill of empty ways
+def test_refill_of_an_empty_cache_leaves_what_the_same_lookups_would_leave():
+    # with room for every id, "lowest empty way in order of first occurrence" is also what a lookup batch does
+    ids = np.random.default_rng(3).permutation(3000)[:900].tolist() + [7, 7, 11]
+    a, b = oracle.Pool(512, 16, 32, 32, 0.5), oracle.Pool(512, 16, 32, 32, 0.5)
+    rc, n_ins = a.emb_refill(ids, 100000)
+    b.emb_lookup(ids, (100000, 4, np.float32), want_out=False)
+    assert rc == 0 and n_ins == len(set(ids)) == b.stats()["inserted"]
+    da, db = a.dump(), b.dump()
+    assert np.array_equal(da["tags"], db["tags"]) and np.array_equal(da["stamps"], db["stamps"])
+    sa = a.stats()
+    assert (sa["lookups"], sa["hits"], sa["misses"], sa["unique_misses"], sa["evicted"], sa["bypassed"]) == (0,) * 6
+    assert sa["inserted"] == n_ins and sa["batch"] == 1  # a refill is a batch of its own in LRU time
+
+
+def test_refill_never_evicts_and_fills_min_of_new_ids_and_empty_ways_per_set():
+    p = oracle.Pool(32, 4, 2, 16, 0.5)  # 4 sets x 8 ways
+    rng = np.random.default_rng(8)
+    p.emb_lookup(rng.integers(0, 40, size=30), (4000, 4, np.float32), want_out=False)
+    before = p.dump()
+    resident = {s: [int(t) for t in before["tags"][s] if t != oracle.TAG_EMPTY] for s in range(p.num_sets)}
+    ids = rng.permutation(np.arange(1000, 1100)).tolist() + [-4, 4000, 5]  # new ids, two invalid, maybe one resident
+    rc, n_ins = p.emb_refill(ids, 4000)
+    after = p.dump()
+    expect = 0
+    for s in range(p.num_sets):
+        kept = before["tags"][s] != oracle.TAG_EMPTY
+        assert np.array_equal(after["tags"][s][kept], before["tags"][s][kept])      # nobody left, nobody moved
+        assert np.array_equal(after["stamps"][s][kept], before["stamps"][s][kept])  # and nobody was touched
+        new_here = []
+        for i in ids:
+            if 0 <= i < 4000 and p.set_of(i) == s and i not in resident[s] and i not in new_here:
+                new_here.append(i)
+        room = p.ways(s) - len(resident[s])
+        got = [int(t) for t, k in zip(after["tags"][s], kept) if not k and t != oracle.TAG_EMPTY]
+        assert got == new_here[:room]  # first come first served, lowest empty way first
+        expect += min(len(new_here), room)
+    assert n_ins == expect and p.stats()["evicted"] == 0
+
+
+def test_refilled_rows_age_between_the_batches_around_them():
+    # one set of 4 ways: A enters in batch 1, B and C by a refill (batch 2), D in batch 3 -> full.
+    # Batch 4 brings two new ids: the victims are A (oldest), then B (refilled, lower way than C).
+    p = oracle.Pool(32, 1, 1, 32, 0.125)
+    assert p.num_sets == 1 and p.ways(0) == 4
+    tab = (1000, 4, np.float32)
+    p.emb_lookup([10], tab, want_out=False)
+    assert p.emb_refill([20, 30], 1000) == (0, 2)
+    p.emb_lookup([40], tab, want_out=False)
+    assert p.dump()["tags"][0][:4].tolist() == [10, 20, 30, 40]
+    assert p.dump()["stamps"][0][:4].tolist() == [1, 2, 2, 3]
+    rc, _, hit = p.emb_lookup([20, 50, 60], tab, want_out=False)  # 20 is resident thanks to the refill
+    assert hit.tolist() == [1, 0, 0]
+    assert p.dump()["tags"][0][:4].tolist() == [50, 20, 60, 40]  # 10 left first, then 30 (20 was just used)
+    assert p.emb_refill([70], 1000) == (0, 0)  # a full set takes nothing
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_refill_against_a_dictionary_model_on_tiny_caches(seed):
+    rng = np.random.default_rng(100 + seed)
+    p = oracle.Pool(16, 4, 2, 4, 0.5)  # 4 sets x 2 ways
+    model = {s: [] for s in range(p.num_sets)}  # resident ids per set in way order (no holes: nothing shrinks here)
+    for step in range(40):
+        ids = rng.integers(-2, 64, size=int(rng.integers(0, 12))).tolist()
+        want = 0
+        for i in ids:
+            if not 0 <= i < 60:
+                continue
+            s = p.set_of(i)
+            if i not in model[s] and len(model[s]) < p.ways(s):
+                model[s].append(i)
+                want += 1
+        rc, n_ins = p.emb_refill(ids, 60)
+        assert (rc, n_ins) == (0, want), step
+        tags = p.dump()["tags"]
+        for s in range(p.num_sets):
+            assert [int(t) for t in tags[s] if t != oracle.TAG_EMPTY] == model[s], (step, s)
