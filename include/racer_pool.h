@@ -137,6 +137,20 @@ int32_t kv_seq_release(racer_pool_t* pool, uint64_t key); /* RACER_EBUSY while p
 int32_t emb_lookup(racer_pool_t* pool, const int64_t* ids, uint64_t n, uint32_t bag, void* out,
                    uint8_t* hit_flags, void* stream);
 
+/* ---- emb_refill (paper Sec. IV-B, last paragraph: after the EMB side has grown, its new
+ *      capacity is filled with hot rows in the background, throttled against the live
+ *      misses' host-to-device traffic) ------------------------------------------------------
+ * ids (dev) int64[n], hottest first (the caller's ranking).  One call is one LRU batch of its
+ * own: every valid id that is not resident when the call starts is fetched from the host
+ * table, once, into the lowest empty way of its set (the k-th such id of a set, by first
+ * occurrence, takes the set's k-th empty way) and stamped with the batch; an id whose set
+ * has no empty way left is skipped.  A refill never evicts, never re-stamps a resident row,
+ * writes no output and counts only in pool_stats.inserted.  It moves at most n * row_bytes
+ * over PCIe: the caller throttles by the size and pacing of its calls (calls on one pool
+ * must not overlap each other or a lookup: they share the pool's work space).
+ * Errors: RACER_EINVAL (NULL pool data, n >= 2^32 - 1), RACER_EHIP. */
+int32_t emb_refill(racer_pool_t* pool, const int64_t* ids, uint64_t n, void* stream);
+
 /* ---- HSTU (paper Sec. II-A/II-B stage "Compute": stacked HSTU blocks that reuse resident
  *      KV state; equations are the published HSTU layer) ------------------------------------ */
 typedef struct {

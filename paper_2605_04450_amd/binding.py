@@ -19,7 +19,7 @@ TAG_EMPTY = 0xFFFFFFFF
 EXPORTS = [
     "pool_create", "pool_destroy", "pool_set_split", "pool_stats", "pool_dump", "emb_cache_dump",
     "pool_num_sets", "pool_slot_of", "kv_seq_reserve", "kv_seq_lookup", "kv_seq_pin", "kv_seq_unpin",
-    "kv_seq_release", "emb_lookup", "hstu_model_create", "hstu_model_destroy", "hstu_step",
+    "kv_seq_release", "emb_lookup", "emb_refill", "hstu_model_create", "hstu_model_destroy", "hstu_step",
     "hstu_attn_paged", "racer_last_error", "racer_prof_enable", "racer_prof_read",
 ]
 PROF_KINDS = ("emb_gather", "emb_miss", "layernorm", "gemm_front", "attention", "gemm_back", "attn_reduce")
@@ -88,6 +88,7 @@ def load():
     for f in (L.kv_seq_pin, L.kv_seq_unpin, L.kv_seq_release):
         f.argtypes = [vp, u64]
     L.emb_lookup.argtypes = [vp, vp, u64, u32, vp, vp, vp]
+    L.emb_refill.argtypes = [vp, vp, u64, vp]
     L.hstu_model_create.argtypes = [C.POINTER(HstuCfg), C.POINTER(HstuWeights), C.POINTER(vp)]
     L.hstu_model_destroy.argtypes = [vp]
     L.hstu_step.argtypes = [vp, vp, C.POINTER(HstuReq), u32, vp, u64, vp, vp, vp, vp]
@@ -224,6 +225,11 @@ def kv_seq_release(pool, key):
 def emb_lookup(pool, ids, out, bag=1, hit_flags=None, stream=None):
     """ids: int64 device tensor [n]; out: device tensor [n/bag][d]; hit_flags: uint8 device tensor [n] or None."""
     return load().emb_lookup(pool, _dp(ids), ids.numel(), bag, _dp(out), _dp(hit_flags), _stream_ptr(stream))
+
+
+def emb_refill(pool, ids, stream=None):
+    """ids: int64 device tensor [n], hottest first."""
+    return load().emb_refill(pool, _dp(ids), ids.numel(), _stream_ptr(stream))
 
 
 def hstu_model_create(L, d, H, elem, page_tokens, n_pos, n_time, n_scale, eps, weights):

@@ -582,7 +582,8 @@ __global__ __launch_bounds__(256) void miss_link(EmbView v, MissWs ws, const int
 // Half a wavefront per unique miss: lane = way.  rank = number of unique misses of the same
 // set that occur earlier in the batch; the miss takes the rank-th victim candidate of the
 // set in (empty ways by index, then (stamp, way) ascending among stamps older than the batch).
-__global__ __launch_bounds__(256) void miss_decide(EmbView v, MissWs ws, uint32_t batch) {
+// With `refill` only empty ways are candidates (a refill never evicts) and only insertions are counted.
+__global__ __launch_bounds__(256) void miss_decide(EmbView v, MissWs ws, uint32_t batch, bool refill) {
   const uint32_t n_unique = ws.ctr[2];
   const uint32_t lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
   const uint32_t wave = (blockIdx.x * 256 + threadIdx.x) >> 6, n_waves = (gridDim.x * 256) >> 6;
@@ -607,7 +608,7 @@ __global__ __launch_bounds__(256) void miss_decide(EmbView v, MissWs ws, uint32_
       tg = v.tags[static_cast<uint64_t>(set) * v.w_max + l32];
       sp = v.stamps[static_cast<uint64_t>(set) * v.w_max + l32];
     }
-    const bool cand = way_ok && (tg == kEmpty || sp < batch);
+    const bool cand = way_ok && (tg == kEmpty || (!refill && sp < batch));
     const unsigned long long key =
         !cand ? ~0ull : (tg == kEmpty ? l32 : ((1ull << 40) | (static_cast<unsigned long long>(sp) << 5) | l32));
     uint32_t pos = 0;
@@ -619,7 +620,10 @@ __global__ __launch_bounds__(256) void miss_decide(EmbView v, MissWs ws, uint32_
     const uint32_t mine = half ? static_cast<uint32_t>(vm >> 32) : static_cast<uint32_t>(vm);
     const int32_t way = mine ? __ffs(mine) - 1 : -1;
     const uint32_t victim_tag = __shfl(tg, half * 32 + (way >= 0 ? way : 0), kWave);
-    if (act && l32 == 0) {
+    if (act && l32 == 0 && refill) {
+      ws.u_way[u] = way;
+      if (way >= 0) atomicAdd(&v.counters[ctr_index(kCtrInserted)], 1ull);
+    } else if (act && l32 == 0) {
       ws.u_way[u] = way;
       atomicAdd(&v.counters[ctr_index(kCtrUnique)], 1ull);
       if (way >= 0) {
@@ -644,7 +648,8 @@ __global__ __launch_bounds__(256) void miss_resolve(MissWs ws, const int64_t* __
 
 // Apply the decisions: new tag and stamp, then one read of the row from the pinned host
 // table (zero-copy over PCIe) into the staging row and, if inserted, into the pool slot.
-__global__ __launch_bounds__(256) void miss_apply_fetch(EmbView v, MissWs ws, uint32_t batch) {
+// With `refill` nobody waits for the row: it is fetched only if it enters the cache, and not staged.
+__global__ __launch_bounds__(256) void miss_apply_fetch(EmbView v, MissWs ws, uint32_t batch, bool refill) {
   const uint32_t n_unique = ws.ctr[2];
   const uint32_t lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
   const uint32_t wave = (blockIdx.x * 256 + threadIdx.x) >> 6, n_waves = (gridDim.x * 256) >> 6;
@@ -654,6 +659,7 @@ __global__ __launch_bounds__(256) void miss_apply_fetch(EmbView v, MissWs ws, ui
     if (u >= n_unique) continue;
     const uint32_t id32 = ws.u_id[u], set = ws.u_set[u];
     const int32_t way = ws.u_way[u];
+    if (refill && way < 0) continue;
     uint8_t* dst = nullptr;
     if (way >= 0) {
       dst = v.base + slot_offset(v, set, static_cast<uint32_t>(way));
@@ -666,7 +672,7 @@ __global__ __launch_bounds__(256) void miss_apply_fetch(EmbView v, MissWs ws, ui
     uint8_t* stg = ws.staging + static_cast<uint64_t>(u) * v.row_bytes;
     for (uint32_t c = l32; c < chunks; c += 32) {
       const uint4 val = *reinterpret_cast<const uint4*>(src + 16 * c);
-      *reinterpret_cast<uint4*>(stg + 16 * c) = val;
+      if (!refill) *reinterpret_cast<uint4*>(stg + 16 * c) = val;
       if (dst) *reinterpret_cast<uint4*>(dst + 16 * c) = val;
     }
   }
@@ -685,6 +691,31 @@ __global__ __launch_bounds__(256) void emb_deferred_gather(EmbView v, MissWs ws,
     const uint64_t o = ws.def_list[k];
     emit_row(v, ws, bag, lpr, sub, out + o * v.row_bytes,
              [&](uint32_t f) { return ws.loc[o * bag + f]; });
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Refill of empty ways (paper Sec. IV-B: new EMB capacity is filled with hot rows in the
+// background).  The probe only finds out which ids are not resident: half a wavefront per id,
+// lane = way, one coalesced read of the set's tag line; nothing is stamped and nothing is
+// written out.  The ids that are not resident then take the miss path with `refill` set.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void emb_refill_probe(EmbView v, MissWs ws, const int64_t* __restrict__ ids, uint32_t n) {
+  const uint32_t lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
+  const uint32_t wave = (blockIdx.x * 256 + threadIdx.x) >> 6, n_waves = (gridDim.x * 256) >> 6;
+  if (blockIdx.x == 0 && threadIdx.x < 3) ws.ctr_next[threadIdx.x] = 0;  // the next call's list counters
+  for (uint32_t i0 = wave * 2; i0 < n; i0 += n_waves * 2) {
+    const uint32_t i = i0 + half;
+    const int64_t id = i < n ? ids[i] : -1;
+    const bool valid = id >= 0 && static_cast<uint64_t>(id) < v.rows;
+    bool match = false;
+    if (valid) {
+      const uint32_t set = set_of(v, id);
+      if (l32 < ways_of(v, set)) match = v.tags[static_cast<uint64_t>(set) * v.w_max + l32] == static_cast<uint32_t>(id);
+    }
+    const unsigned long long m = __ballot(match);
+    const bool resident = (half ? static_cast<uint32_t>(m >> 32) : static_cast<uint32_t>(m)) != 0;
+    if (l32 == 0 && valid && !resident) ws.miss_list[atomicAdd(&ws.ctr[0], 1u)] = i;
   }
 }
 
@@ -830,10 +861,23 @@ hipError_t launch_emb_miss_path(const EmbView& v, const MissWs& ws, const int64_
   const uint32_t mblocks = n / 256 + 1 < 1024 ? n / 256 + 1 : 1024;
   hipLaunchKernelGGL(miss_dedupe, dim3(mblocks), dim3(256), 0, stream, ws, ids, batch);
   hipLaunchKernelGGL(miss_link, dim3(mblocks), dim3(256), 0, stream, v, ws, ids, batch);
-  hipLaunchKernelGGL(miss_decide, dim3(mblocks), dim3(256), 0, stream, v, ws, batch);
+  hipLaunchKernelGGL(miss_decide, dim3(mblocks), dim3(256), 0, stream, v, ws, batch, false);
   hipLaunchKernelGGL(miss_resolve, dim3(mblocks), dim3(256), 0, stream, ws, ids, batch);
-  hipLaunchKernelGGL(miss_apply_fetch, dim3(mblocks), dim3(256), 0, stream, v, ws, batch);
+  hipLaunchKernelGGL(miss_apply_fetch, dim3(mblocks), dim3(256), 0, stream, v, ws, batch, false);
   hipLaunchKernelGGL(emb_deferred_gather, dim3(mblocks), dim3(256), 0, stream, v, ws, bag, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_emb_refill(const EmbView& v, const MissWs& ws, const int64_t* ids, uint32_t n, uint32_t batch,
+                             hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  const uint32_t pblocks = n / 8 + 1 < 2048 ? n / 8 + 1 : 2048;  // two ids per wavefront and pass
+  const uint32_t mblocks = n / 256 + 1 < 1024 ? n / 256 + 1 : 1024;
+  hipLaunchKernelGGL(emb_refill_probe, dim3(pblocks), dim3(256), 0, stream, v, ws, ids, n);
+  hipLaunchKernelGGL(miss_dedupe, dim3(mblocks), dim3(256), 0, stream, ws, ids, batch);
+  hipLaunchKernelGGL(miss_link, dim3(mblocks), dim3(256), 0, stream, v, ws, ids, batch);
+  hipLaunchKernelGGL(miss_decide, dim3(mblocks), dim3(256), 0, stream, v, ws, batch, true);
+  hipLaunchKernelGGL(miss_apply_fetch, dim3(mblocks), dim3(256), 0, stream, v, ws, batch, true);
   return hipGetLastError();
 }
 

@@ -68,6 +68,10 @@ hipError_t launch_emb_probe(const EmbView& v, const MissWs& ws, const int64_t* i
 hipError_t launch_emb_miss_path(const EmbView& v, const MissWs& ws, const int64_t* ids, uint32_t n, uint32_t bag,
                                 uint8_t* out, uint32_t batch, hipStream_t stream);
 
+// refill of empty ways with `ids` (hottest first): probe, then the miss path restricted to empty ways
+hipError_t launch_emb_refill(const EmbView& v, const MissWs& ws, const int64_t* ids, uint32_t n, uint32_t batch,
+                             hipStream_t stream);
+
 hipError_t launch_emb_shrink(const EmbView& v, uint32_t old_full, uint32_t old_part_sets,
                              hipStream_t stream);
 

@@ -422,6 +422,24 @@ int32_t emb_lookup(racer_pool_t* p, const int64_t* ids, uint64_t n, uint32_t bag
   return RACER_OK;
 }
 
+int32_t emb_refill(racer_pool_t* p, const int64_t* ids, uint64_t n, void* stream_v) {
+  if (!p || !p->device || !p->d_table) return RACER_EINVAL;
+  if (n >= 0xFFFFFFFFull || (n && !ids)) return RACER_EINVAL;
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  p->batch += 1;  // a batch of its own in LRU time (and a fresh key for the dedupe table)
+  if (n == 0) return RACER_OK;
+  int32_t rc = ensure_miss_ws(p, n);
+  if (rc) return rc;
+  racer::MissWs ws = p->ws;
+  ws.ctr = p->ws_ctr + 4 * (p->launches & 1);
+  ws.ctr_next = p->ws_ctr + 4 * ((p->launches + 1) & 1);
+  p->launches += 1;
+  p->last_stream = stream;
+  ProfScope t(p, RACER_PROF_EMB_MISS, stream);
+  HIP_TRY(racer::launch_emb_refill(p->view(), ws, ids, static_cast<uint32_t>(n), p->batch, stream));
+  return RACER_OK;
+}
+
 // ---- HSTU ---------------------------------------------------------------------------------
 
 int32_t hstu_model_create(const racer_hstu_cfg* cfg, const racer_hstu_weights* w, racer_hstu_t** out) {

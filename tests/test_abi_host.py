@@ -63,6 +63,7 @@ def same_state(h, o):
 def test_metadata_only_pool_rejects_device_calls():
     h = host_pool(64, 4, 8, 32, 0.5)
     assert B.load().emb_lookup(h, None, 0, 1, None, None, None) == B.EINVAL
+    assert B.load().emb_refill(h, None, 0, None) == B.EINVAL
     assert B.load().emb_cache_dump(h, None, None) == B.EINVAL
     B.pool_destroy(h)
 

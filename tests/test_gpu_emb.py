@@ -199,3 +199,57 @@ def test_growth_is_deferred_when_kv_pages_are_pinned():
     assert (rc, ach) == orc.set_split(0.9) and rc == B.DEFERRED and ach < 0.9
     check_state(pool, orc, table, "deferred")
     pool.close()
+
+
+def refill_both(pool, orc, ids, rows):
+    rc = B.emb_refill(pool.h, torch.from_numpy(np.asarray(ids, dtype=np.int64)).to(Hn.DEV))
+    assert rc == B.OK, B.last_error()
+    rco, n_ins = orc.emb_refill(ids, rows)
+    assert rco == oracle.OK
+    return n_ins
+
+
+@pytest.mark.parametrize("n_pages,spp,w_max,frac,rows,n", [
+    (128, 8, 32, 0.5, 6000, 700),     # 32 sets of 16 ways: sets overflow, most ids are skipped
+    (512, 32, 32, 0.5, 100000, 5000),  # roomy: nearly every id finds an empty way
+    (64, 8, 16, 0.3, 900, 333),       # uneven ways (4 or 5), ragged tail of the id list
+    (16, 4, 2, 0.5, 200, 1),          # one way per set, a single id
+])
+def test_refill_fills_empty_ways_only_like_the_oracle(n_pages, spp, w_max, frac, rows, n):
+    rng = np.random.default_rng(n_pages * 7 + n)
+    d = 16
+    table = rng.standard_normal((rows, d)).astype(np.float32)
+    pool, orc = make_pair(n_pages, spp * d * 4, d, False, 4, w_max, table, frac)
+    run_batches(pool, orc, table, [rng.integers(0, rows, size=max(n // 2, 1))], tag="before")
+    for k in range(3):
+        ids = rng.integers(-3, rows + 3, size=n)  # duplicates, resident ids and ids outside the table included
+        ins = refill_both(pool, orc, ids, rows)
+        check_state(pool, orc, table, "refill %d (%d rows)" % (k, ins))
+    # empty list: still a batch of its own
+    refill_both(pool, orc, np.zeros(0, dtype=np.int64), rows)
+    run_batches(pool, orc, table, [rng.integers(0, rows, size=n + 5) for _ in range(3)], tag="after")
+    pool.close()
+
+
+def test_refill_after_growth_restores_hits_without_evicting():
+    # shrink the hot cache, grow it again (the new ways come back empty), refill them with the hottest ids
+    rng = synth.rng_for(0, 9)
+    rows, d = 50000, 64
+    table = synth.make_table(rng, rows, d, bf16=True)
+    pool, orc = make_pair(512, 16384, d, True, 16, 32, table, 0.6)
+    run_batches(pool, orc, table, [synth.zipf_ids(rng, rows, 1.0, 4096) for _ in range(6)], tag="warm")
+    for frac in (0.2, 0.6):
+        rc, ach = B.pool_set_split(pool.h, frac)
+        assert (rc, ach) == orc.set_split(frac)
+    check_state(pool, orc, table, "after the moves")
+    before = pool.stats()
+    hot = synth.ranks_to_rows(np.arange(1, 20001), rows)  # the 20 000 hottest rows, hottest first
+    total = 0
+    for lo in range(0, len(hot), 3000):  # throttled: a chunk at a time
+        total += refill_both(pool, orc, hot[lo: lo + 3000], rows)
+        check_state(pool, orc, table, "chunk at %d" % lo)
+    after = pool.stats()
+    assert after["inserted"] - before["inserted"] == total > 0
+    assert after["evicted"] == before["evicted"] and after["lookups"] == before["lookups"]
+    run_batches(pool, orc, table, [synth.zipf_ids(rng, rows, 1.0, 4096) for _ in range(2)], tag="served")
+    pool.close()
