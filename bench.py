@@ -58,6 +58,13 @@ CONFIGS = {
                             "8192 users (Zipf 0.6 popularity, lognormal 512..12k histories), batches of 128 requests, "
                             "64 new tokens on a KV hit, full recompute otherwise, 8 sum-pooled features per token "
                             "(disjoint row ranges, Zipf(0.9) each)"),
+    # Refill after growth: the hot cache grows from 0.2 to 0.5 of the pool (the new ways are empty) while lookup
+    # batches keep coming; the empty ways are left to the live misses, filled at once, or filled a budget at a time
+    "refill": dict(index=6, d=256, L=4, rows=50_000_000, pool_bytes=64 << 30, pt=64, alpha=0.8, zipf=0.9,
+                   lookups=262144, batches=300, budget_mb=48, period_ms=4.0, refill_bench=True,
+                   desc="Refill after growth 0.2 -> 0.5: 64 GiB pool, table 50Mx256 bf16 pinned host, batches of 262144 "
+                        "Zipf(0.9) lookups arriving every 4 ms; no refill / one unthrottled refill / 48 MB of refill "
+                        "per interval less the interval's live miss bytes"),
     "tiny": dict(index=0, L=1, d=64, H=2, bf16=False, rows=100_000, pool_bytes=4 << 20, pt=16, alpha=0.5,
                  batch=4, mean_len=256, min_len=256, max_len=256, zipf=1.0, n_time=32, warm_batches=4,
                  desc="Tiny: 1 layer d=64 H=2 fp32, table 100k x 64 fp32, 4 MiB pool, 4 x 256 tokens, KV page 16"),
@@ -437,6 +444,105 @@ def alpha_curve_bench(args, c, torch, Hn, B, synth):
     model.close()
 
 
+def refill_bench(args, c, torch, Hn, B, synth):
+    """Latency of live lookup batches while the empty ways of a grown hot cache are refilled (paper Sec. IV-B: the
+    refill shares the host link with the live misses and is throttled against them).  Batches arrive at a fixed
+    period; refill work is queued behind a batch for the gap before the next one.  Three policies from the same
+    starting state; per policy the batch latency (arrival to completion), the hit rate over time and the bytes each
+    side moved."""
+    dev = Hn.DEV
+    d, pt, L = c["d"], c["pt"], c["L"]
+    rows = c["rows"]
+    table = None
+    while table is None:
+        try:
+            table = torch.empty((rows, d), dtype=torch.int16, pin_memory=True)
+        except RuntimeError:
+            rows //= 2  # the host cannot pin that much: halve the table (said in the output)
+    synth.fill_table_bf16_torch(table, synth.SEED_BASE + c["index"], dev)
+    torch.cuda.synchronize()
+    R = d * 2
+    page_size = pt * 2 * L * d * 2
+    n_pages = c["pool_bytes"] // page_size
+    n, K = c["lookups"], c["batches"]
+    out = torch.empty((n, d), dtype=torch.bfloat16, device=dev)
+    hot = torch.from_numpy(synth.ranks_to_rows(np.arange(1, rows + 1), rows)).to(dev)  # every row, hottest first
+    chunk = 65536  # ids per refill call: at most 32 MB over the link
+    results = []
+    for policy in ("none", "unthrottled", "throttled"):
+        rng = synth.rng_for(c["index"], 1)  # the same id stream for every policy
+        pool = Hn.Pool(n_pages, page_size, R, B.ELEM_BF16, pt, 32, table.view(torch.bfloat16), c["alpha"], zero_fill=False)
+        for lo in range(0, rows, n):  # every row once, then a Zipf stream that sets the LRU order
+            assert B.emb_lookup(pool.h, hot[lo: lo + n], out, 1, None) == B.OK, B.last_error()
+        warm = [torch.from_numpy(synth.zipf_ids(rng, rows, c["zipf"], n)).to(dev) for _ in range(30)]
+        for ids in warm:
+            assert B.emb_lookup(pool.h, ids, out, 1, None) == B.OK, B.last_error()
+        assert B.pool_set_split(pool.h, 0.2)[0] == B.OK
+        for ids in warm[:10]:
+            assert B.emb_lookup(pool.h, ids, out, 1, None) == B.OK, B.last_error()
+        rc, ach = B.pool_set_split(pool.h, 0.5)
+        assert rc == B.OK, (rc, B.last_error())
+        torch.cuda.synchronize()
+        batches = [torch.from_numpy(synth.zipf_ids(rng, rows, c["zipf"], n)).to(dev) for _ in range(K)]
+        st0 = pool.stats()
+        cursor, budget_rows = 0, c["budget_mb"] * 1000000 // R
+        lat, hit_rate = [], []
+        prev, live_last, yield_last, refill_rows = st0, 0, 1.0, 0
+        t_begin = time.perf_counter()
+        period = c["period_ms"] * 1e-3
+        issued = 0
+        for k in range(K):
+            # batch k arrives at t_begin + k * period whatever the device is doing; its latency runs from then
+            arrival = t_begin + k * period
+            while time.perf_counter() < arrival:
+                pass
+            assert B.emb_lookup(pool.h, batches[k], out, 1, None) == B.OK, B.last_error()
+            torch.cuda.synchronize()
+            lat.append(time.perf_counter() - arrival)
+            st = pool.stats()
+            hit_rate.append((st["hits"] - prev["hits"]) / n)
+            live_last = st["unique_misses"] - prev["unique_misses"]
+            entered = (st["inserted"] - prev["inserted"]) - (live_last - (st["bypassed"] - prev["bypassed"]))
+            refill_rows += entered
+            if issued:
+                yield_last = entered / issued
+            prev = st
+            # refill work for the gap before the next arrival (it runs behind this batch on the same stream)
+            if policy == "unthrottled" and k == 0:
+                want = rows
+            elif policy == "throttled":
+                # the interval's budget, less what the live misses of this batch took from the link, in ids:
+                # the last interval's yield (rows that entered per id offered) turns rows into ids
+                want = int(max(budget_rows - live_last, 0) / max(yield_last, 0.05))
+            else:
+                want = 0
+            issued = 0
+            while cursor < rows and issued < want:
+                assert B.emb_refill(pool.h, hot[cursor: cursor + chunk]) == B.OK, B.last_error()
+                issued += min(chunk, rows - cursor)
+                cursor += chunk
+        total_s = time.perf_counter() - t_begin
+        st1 = pool.stats()
+        live_rows = st1["unique_misses"] - st0["unique_misses"]
+        refilled = refill_rows
+        lat_ms = np.array(lat) * 1e3
+        reach = next((k for k, h in enumerate(hit_rate) if h >= 0.999), None)
+        results.append({"policy": policy, "p50_ms": float(np.percentile(lat_ms, 50)), "p99_ms": float(np.percentile(lat_ms, 99)),
+                        "max_ms": float(lat_ms.max()), "total_s": total_s, "first_hit_rate": hit_rate[0],
+                        "last_hit_rate": hit_rate[-1], "batches_to_0.999": reach,
+                        "live_miss_MB": live_rows * R / 1e6, "refill_MB": refilled * R / 1e6})
+        print("refill %s" % json.dumps(results[-1]), file=sys.stderr, flush=True)
+        pool.close()
+        del pool
+    thr = results[2]
+    print(json.dumps({
+        "metric": "emb_lookup_p99_ms_during_throttled_refill", "value": thr["p99_ms"], "unit": "ms per batch of %d lookups" % n,
+        "n_gpus": 1, "steps": K, "warmup": 0, "ms_per_step": thr["p50_ms"], "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": c["desc"], "table_rows": rows, "pages": int(n_pages), "budget_MB_per_interval": c["budget_mb"]},
+        "policies": results}))
+
+
 def one_step(wl, k, B):
     ids = wl["ids_dev"][k % len(wl["ids_dev"])]
     rc = B.emb_lookup(wl["pool"].h, ids, wl["x"], 1, None)
@@ -521,6 +627,9 @@ def main():
         return
     if c.get("alpha_curve"):
         alpha_curve_bench(args, c, torch, Hn, B, synth)
+        return
+    if c.get("refill_bench"):
+        refill_bench(args, c, torch, Hn, B, synth)
         return
     wl = build_workload(c, torch, Hn, B, synth)
     pool = wl["pool"]
