@@ -9,6 +9,7 @@ Prints ONE JSON line.  `--config tiny` runs the small fp32
 configuration instead (used for quick checks).
 """
 import argparse
+import math
 import json
 import os
 import sys
@@ -365,6 +366,9 @@ def alpha_curve_bench(args, c, torch, Hn, B, synth):
         user_of_rank = rng.permutation(users)
         sweep_n = 1 << 19
         out_sweep = torch.empty((sweep_n, d), dtype=torch.bfloat16, device=dev)
+        per = rows // c["bag"]  # the hottest rows of every feature range, hottest first, for refills after a growth
+        hot = torch.from_numpy((synth.ranks_to_rows(np.arange(1, per + 1), per)[:, None]
+                                + np.arange(c["bag"], dtype=np.int64)[None, :] * per).reshape(-1)).to(dev)
         # warm the hot cache: one pass over the table, then a Zipf stream that sets the LRU order
         for lo in range(0, rows, sweep_n):
             ids = torch.arange(lo, lo + sweep_n, dtype=torch.int64, device=dev) % rows
@@ -412,10 +416,15 @@ def alpha_curve_bench(args, c, torch, Hn, B, synth):
             hits = sum(1 for p_ in prefix if p_ > 0)
             return len(picked), len(keys), hits, N, t1 - t0, t2 - t1
 
-        points = []
-        for alpha in grid:
+        def measure(alpha, tag):
+            """Move the boundary (refilling what a growth left empty), let the caches settle, time args.steps batches."""
+            grows = alpha > pool.stats()["pages_emb"] / n_pages + 1e-6
             rc, ach = B.pool_set_split(pool.h, alpha)
             assert rc in (B.OK, B.DEFERRED), (rc, B.last_error())
+            if grows:
+                slots = int(pool.stats()["pages_emb"]) * (page_size // (d * 2))
+                for lo in range(0, min(slots, hot.numel()), sweep_n):
+                    assert B.emb_refill(pool.h, hot[lo: lo + sweep_n]) == B.OK, B.last_error()
             for _ in range(args.warmup):
                 serve(False)
             st0 = pool.stats()
@@ -424,18 +433,44 @@ def alpha_curve_bench(args, c, torch, Hn, B, synth):
                 acc += np.array(serve(True), dtype=np.float64)
             st1 = pool.stats()
             lookups = st1["lookups"] - st0["lookups"]
-            points.append({"alpha": alpha, "achieved": ach, "kv_hit_rate": acc[2] / max(acc[1], 1),
-                           "dropped_requests": int(acc[0] - acc[1]),
-                           "emb_hit_rate": (st1["hits"] - st0["hits"]) / max(lookups, 1),
-                           "miss_MB_per_step": (st1["unique_misses"] - st0["unique_misses"]) * d * 2 / 1e6 / args.steps,
-                           "new_tokens_per_step": acc[3] / args.steps, "emb_ms": 1e3 * acc[4] / args.steps,
-                           "hstu_ms": 1e3 * acc[5] / args.steps, "total_ms": 1e3 * (acc[4] + acc[5]) / args.steps})
-            print("alphacurve mean %d: %s" % (mean_len, json.dumps(points[-1])), file=sys.stderr, flush=True)
+            pt_ = {"alpha": alpha, "achieved": ach, "kv_hit_rate": acc[2] / max(acc[1], 1),
+                   "dropped_requests": int(acc[0] - acc[1]),
+                   "emb_hit_rate": (st1["hits"] - st0["hits"]) / max(lookups, 1),
+                   "miss_MB_per_step": (st1["unique_misses"] - st0["unique_misses"]) * d * 2 / 1e6 / args.steps,
+                   "new_tokens_per_step": acc[3] / args.steps, "emb_ms": 1e3 * acc[4] / args.steps,
+                   "hstu_ms": 1e3 * acc[5] / args.steps, "total_ms": 1e3 * (acc[4] + acc[5]) / args.steps}
+            print("alphacurve mean %d %s: %s" % (mean_len, tag, json.dumps(pt_)), file=sys.stderr, flush=True)
+            return pt_
+
+        points = [measure(alpha, "grid") for alpha in grid]
         best = min(points, key=lambda q: q["total_ms"])
+        # Closed loop (the paper's Sec. IV-A controller picks a step from {0, +-0.05, +-0.1} each round; its trained
+        # policy is not available, so a hill climb on the measured step time stands in): from 0.8, each round tries
+        # the short step in the current direction, then the long one (which carries it over a flat stretch), then,
+        # once, the short step the other way; a move is kept if the time falls by more than 0.5 %; no move kept = stop.
+        alpha, cur, sign, path = 0.8, measure(0.8, "ctl"), -1.0, []
+        path.append({"alpha": alpha, "total_ms": float(cur["total_ms"]), "accepted": True})
+        for _ in range(14):
+            moved = False
+            for delta in (0.05 * sign, 0.1 * sign, -0.05 * sign):
+                nxt = round(min(0.8, max(0.2, alpha + delta)), 2)
+                if nxt == alpha or any(q["alpha"] == nxt and not q["accepted"] for q in path[-3:]):
+                    continue
+                cand = measure(nxt, "ctl")
+                ok = bool(cand["total_ms"] < cur["total_ms"] * 0.995)
+                path.append({"alpha": nxt, "total_ms": float(cand["total_ms"]), "accepted": ok})
+                if ok:
+                    alpha, cur, moved = nxt, cand, True
+                    sign = math.copysign(1.0, delta)
+                    break
+            if not moved:
+                break
+        if path[-1]["alpha"] != alpha:  # leave the pool at the split the controller settled on
+            B.pool_set_split(pool.h, alpha)
         curves.append({"mean_history": int(mean_len), "best_alpha": best["alpha"], "best_total_ms": best["total_ms"],
-                       "points": points})
+                       "points": points, "controller_path": path, "controller_alpha": alpha})
         pool.close()
-        del pool, out_sweep
+        del pool, out_sweep, hot
     print(json.dumps({
         "metric": "serving_step_ms_at_best_split", "value": curves[0]["best_total_ms"], "unit": "ms per batch of %d requests" % c["batch"],
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": curves[0]["best_total_ms"],
