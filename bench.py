@@ -43,6 +43,12 @@ CONFIGS = {
                       attn_only=True,
                       desc="Long history KV reuse: 8 layers d=512 H=8 bf16, 32 requests x (16384 cached + 512 new) tokens, "
                            "KV page 64 tokens; paged attention of one layer only"),
+    # The same shape through hstu_step: all 8 layers, new K,V appended behind a cached prefix (random values stand in
+    # for the cached keys and values; zeros would do for the arithmetic but let the chip clock higher)
+    "longstep": dict(index=2, L=8, d=512, H=8, bf16=True, pt=64, batch=32, prefix=16384, new=512, n_time=32,
+                     long_step=True,
+                     desc="Long history KV reuse, whole step: 8 layers d=512 H=8 bf16, 32 requests x (16384 cached + 512 "
+                          "new) tokens, KV page 64 tokens (1 MiB pages), pages shuffled"),
     # Split sweep: the boundary moves in steps of 0.05 down from 0.8 to 0.2 (each step evicts and compacts the
     # hot cache) and back up (metadata only), with lookup batches after every move
     "sweep": dict(index=4, L=4, d=256, H=4, bf16=True, rows=100_000_000, pool_bytes=128 << 30, pt=64, alpha=0.8,
@@ -253,6 +259,66 @@ def attn_only_bench(args, c, torch, Hn, B, synth):
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": c["desc"], "new_tokens_per_step": int(N), "causal_pairs": pairs},
+        "roofline": {"kernel": "attention_bf16_mfma", "bound": "mfma", "achieved": tf, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": tf / PEAK_BF16_TFLOPS, "traffic": None, "flop_per_launch": flop,
+                     "ms_per_launch": attn_ms},
+        "kernels": {k: {"ms_per_launch": (v[0] / v[1] if v[1] else 0.0), "launches_per_step": v[1] / args.steps}
+                    for k, v in prof.items() if v[1]},
+    }))
+    model.close()
+    pool.close()
+
+
+def long_step_bench(args, c, torch, Hn, B, synth):
+    """hstu_step on cached prefixes: every layer's front half, paged attention against prefix + new keys, back half."""
+    dev = Hn.DEV
+    L, d, H, pt, P, T, Bq = c["L"], c["d"], c["H"], c["pt"], c["prefix"], c["new"], c["batch"]
+    n_pos = P + T
+    rng = synth.rng_for(c["index"])
+    w = synth.make_weights(rng, L, d, H, n_pos, c["n_time"], True)
+    model = Hn.Model(L, d, H, B.ELEM_BF16, pt, n_pos, c["n_time"], float(n_pos), w)
+    page = model.page_size()
+    pages_per_req = (P + T + pt - 1) // pt
+    n_pages = ((Bq * pages_per_req * 4 // 3) // 32 + 1) * 32
+    pool = Hn.Pool(n_pages, page, d * 2, B.ELEM_BF16, pt, 32, None, 0.25, zero_fill=False)
+    first_kv = n_pages // 4
+    perm = first_kv + rng.permutation(n_pages - first_kv)
+    reqs, n_pt, n_ts, N = synth.make_requests([P] * Bq, [T] * Bq, pt)
+    pts = torch.from_numpy(perm[:n_pt].astype(np.int32)).to(dev)
+    ts = torch.from_numpy(np.concatenate([synth.timestamps(rng, P + T) for _ in range(Bq)])).to(dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4321)
+    for piece in pool.mem.view(torch.bfloat16).split(1 << 28):  # every page: N(0, 0.35^2) keys and values
+        piece.copy_(torch.randn(piece.numel(), generator=gen, device=dev) * 0.35)
+    x = (torch.randn((N, d), generator=gen, device=dev) * 0.5).to(torch.bfloat16)
+    y = torch.empty_like(x)
+    reqs_c = (B.make_reqs(reqs), len(reqs))
+
+    def call():
+        rc = B.hstu_step(pool.h, model.h, reqs_c, pts, x, ts, y)
+        assert rc == B.OK, (rc, B.last_error())
+    for _ in range(args.warmup):
+        call()
+    torch.cuda.synchronize()
+    B.racer_prof_enable(pool.h, 1)
+    B.racer_prof_read(pool.h)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        call()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = B.racer_prof_read(pool.h)
+    B.racer_prof_enable(pool.h, 0)
+    pairs = float(Bq) * (T * P + T * (T + 1) / 2)
+    flop = 4.0 * d * pairs
+    attn_ms = prof["attention"][0] / max(prof["attention"][1], 1)
+    tf = flop / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else 0.0
+    ms = dt * 1e3 / args.steps
+    print(json.dumps({
+        "metric": "hstu_step_tokens_per_s", "value": N / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": c["desc"], "new_tokens_per_step": int(N), "causal_pairs_per_layer": pairs},
         "roofline": {"kernel": "attention_bf16_mfma", "bound": "mfma", "achieved": tf, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": tf / PEAK_BF16_TFLOPS, "traffic": None, "flop_per_launch": flop,
                      "ms_per_launch": attn_ms},
@@ -656,6 +722,9 @@ def main():
         return
     if c.get("attn_only"):
         attn_only_bench(args, c, torch, Hn, B, synth)
+        return
+    if c.get("long_step"):
+        long_step_bench(args, c, torch, Hn, B, synth)
         return
     if c.get("split_sweep"):
         split_sweep_bench(args, c, torch, Hn, B, synth)
