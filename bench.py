@@ -697,8 +697,8 @@ def cpu_baseline(c, wl, synth, budget_tokens):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="mid", choices=sorted(CONFIGS))
     ap.add_argument("--cpu-tokens", type=int, default=None, help="token budget of the oracle sample")
     ap.add_argument("--no-cpu", action="store_true")
