@@ -385,22 +385,22 @@ __global__ __launch_bounds__(256) void gemm_front_bf16(HstuDims hd, uint32_t lay
   }
 }
 
-// fp32 GEMM for the small configuration: one thread per output, W is [K][Nout]
 // ---------------------------------------------------------------------------------------
 // Fused layer halves for bf16 models with d = KD <= 256 (one kernel each, no normalised copy
 // of the activations in memory):
 //   FRONT: [U|V|Q|K] = SiLU(LN1(X) W1 + b1), U and Q*log2(e) to row-major buffers, K and V into
 //          the pages;
 //   BACK:  Y = X + (LN2(O) * U) W2 + b2.
-// A wavefront owns 32 token rows.  Their activations are loaded once, normalised in registers
-// (a row is split over the two lanes (g = 0, 1) that share the token: two cross-lane sums) and
-// kept as the token-side MFMA operand for the whole sweep over the output columns, KD/16
-// fragments of 8 elements.  The weights (stored transposed, [out][KD]) pass through LDS in
+// A wavefront owns 32 token rows.  Their activations are loaded once (whole-line loads, dealt
+// out to the lanes through LDS), normalised in registers (a row is split over the two lanes
+// (g = 0, 1) that share the token: two cross-lane sums) and kept as the token-side MFMA operand
+// for the whole sweep over the output columns, KD/16 fragments of 8 elements.  The weights (stored transposed, [out][KD]) pass through LDS in
 // tiles of 32 output columns, double buffered with one barrier per tile; chunk c of tile row R
 // sits at chunk position c ^ (R & 7) so that the operand reads of eight neighbouring lanes
 // (eight rows, same c) hit different banks.  The product is taken as (W tile) x (X^T), so a
-// lane ends up with one token and 16 output features (four runs of four), which gives 8-byte
-// stores for row-major outputs and K, and lane-coalesced 2-byte stores for V^T.
+// lane ends up with one token and 16 output features (four runs of four); row-major outputs and
+// K rows pass through a wave-private LDS tile and leave as 16-byte stores, V^T leaves as
+// lane-coalesced 2-byte stores.
 // WPB = wavefronts per block (a block covers 32 * WPB rows of a row tile of up to 128 rows).
 // ---------------------------------------------------------------------------------------
 struct LayerHalfArgs {
@@ -747,6 +747,7 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
   }
 }
 
+// fp32 GEMM for the small configuration: one thread per output, W is [K][Nout]
 template <typename Epi>
 __global__ __launch_bounds__(256) void gemm_f32_simple(const float* __restrict__ A, const float* __restrict__ W,
                                                        uint32_t M, uint32_t K, uint32_t Nout, Epi epi) {
