@@ -192,8 +192,14 @@ int32_t hstu_model_destroy(racer_hstu_t* model);
  * non-decreasing per request; out (dev) [N][d].  For every layer the new tokens' K,V are
  * written into the request's pages at positions prefix_len.., then every new token attends
  * to positions 0..its own through the page table.  Page ids outside the pool are skipped
- * and counted in bad_pages.  Errors: RACER_EINVAL (shape mismatch with the pool, offsets
- * beyond n_page_entries), RACER_ENOMEM/RACER_EHIP (workspace). */
+ * and counted in bad_pages.  The work is ordered on `stream` as usual: what the caller
+ * queues behind the call sees the finished outputs.  Inside, a bf16 batch of 32 768 or more
+ * new tokens (d = 128 or 256) runs as two pipelines over two runs of requests, the second
+ * on a stream of the pool's own (default priority) that forks from `stream` at the start
+ * and joins it at the end; results do not depend on it.  While racer_prof_enable is on,
+ * the step runs as one pipeline so that kernel durations do not overlap.
+ * Errors: RACER_EINVAL (shape mismatch with the pool, offsets beyond n_page_entries),
+ * RACER_ENOMEM/RACER_EHIP (workspace). */
 int32_t hstu_step(racer_pool_t* pool, racer_hstu_t* model, const racer_hstu_req* reqs, uint32_t B,
                   const int32_t* kv_page_tables, uint64_t n_page_entries, const void* x_in,
                   const int64_t* ts, void* out, void* stream);

@@ -116,6 +116,9 @@ struct racer_pool {
   uint64_t hp_cap = 0;  // fp32 partial outputs of split attention items
   uint8_t* hp_dev = nullptr;
   Staging hstage;
+  // second stream of a step that runs as two pipelines (default priority), with its fork and join events
+  hipStream_t aux_stream = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   // optional per-kernel-class timing with events on the caller's stream
   struct ProfMark { hipEvent_t a, b; int kind; };
   bool prof_on = false;
@@ -292,6 +295,12 @@ int32_t pool_destroy(racer_pool_t* p) {
       (void)hipEventDestroy(m.b);
     }
     for (hipEvent_t e : p->prof_spare) (void)hipEventDestroy(e);
+    if (p->aux_stream) {
+      (void)hipStreamSynchronize(p->aux_stream);
+      (void)hipStreamDestroy(p->aux_stream);
+      (void)hipEventDestroy(p->ev_fork);
+      (void)hipEventDestroy(p->ev_join);
+    }
     (void)hipFree(p->d_tags);
     (void)hipFree(p->d_stamps);
     (void)hipFree(p->d_emb_pages);
@@ -504,17 +513,27 @@ int32_t hstu_model_destroy(racer_hstu_t* m) {
 
 namespace {
 
+// a step with fewer new tokens than this runs as one pipeline (its kernels do not fill the chip twice over)
+#ifndef RACER_SPLIT_MIN_TOKENS
+#define RACER_SPLIT_MIN_TOKENS 32768
+#endif
+constexpr uint64_t kSplitMinTokens = RACER_SPLIT_MIN_TOKENS;
+
 struct StepCtx {
   racer::HstuDims hd;
   racer::KvView kv;
-  racer::StepLists sl;
+  racer::StepLists sl;       // the whole batch
+  racer::StepLists half[2];  // with a split: requests [0, b_split) and [b_split, B), each with lists of its own
+  uint32_t b_split = 0;      // 0: no split
   uint64_t esize;
 };
 
 // Validate the requests, build the row->request map and the attention work lists, ship them
-// to the device on `stream`.
+// to the device on `stream`.  With `want_split` the batch is also cut into two runs of requests with about
+// equal attention work, each with its own work list, groups and row tiles (two pipelines that touch disjoint
+// rows, pages and partial slots), if it has at least two requests.
 int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, uint32_t B, uint64_t n_page_entries,
-                     hipStream_t stream, StepCtx* ctx) {
+                     hipStream_t stream, StepCtx* ctx, bool want_split = false) {
   const racer_hstu_cfg& c = m->cfg;
   if (!p->device || c.page_tokens != p->cfg.page_tokens || c.elem != p->cfg.elem) return RACER_EINVAL;
   const uint64_t esize = c.elem == RACER_ELEM_BF16 ? 2 : 4;
@@ -549,6 +568,20 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
       visits += last / 64 + 1;
     }
   }
+  uint32_t b_split = 0;
+  if (want_split && B >= 2) {
+    // the cut that balances the visits of the two runs best
+    uint64_t acc = 0, best_diff = ~0ull;
+    size_t qi = 0;
+    for (uint32_t r = 0; r + 1 < B; ++r) {
+      while (qi < qtiles.size() && qtiles[qi].req == r) acc += qtiles[qi++].n_kt;
+      const uint64_t diff = acc * 2 > visits ? acc * 2 - visits : visits - acc * 2;
+      if (diff < best_diff) {
+        best_diff = diff;
+        b_split = r + 1;
+      }
+    }
+  }
   const uint64_t block_slots = 1024;  // about 256 CUs x resident blocks
   uint32_t chunk = static_cast<uint32_t>(std::max<uint64_t>(8, (visits * c.H + 2 * block_slots - 1) / (2 * block_slots)));
   // an item's slice of the page table (a chunk and a quarter at most) must fit the kernel's LDS copy
@@ -566,7 +599,7 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
     }
   }
   // units: the items of one request with the same chunk index, for one head
-  struct Unit { uint32_t item0, n_items; uint64_t weight; };
+  struct Unit { uint32_t item0, n_items, req; uint64_t weight; };
   std::vector<racer::AttnItem> items;
   std::vector<Unit> units;
   for (size_t q0 = 0; q0 < qtiles.size();) {
@@ -574,7 +607,7 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
     uint32_t max_ch = 0;
     while (q1 < qtiles.size() && qtiles[q1].req == qtiles[q0].req) max_ch = std::max(max_ch, qtiles[q1++].n_ch);
     for (uint32_t k = 0; k < max_ch; ++k) {
-      Unit u{static_cast<uint32_t>(items.size()), 0, 0};
+      Unit u{static_cast<uint32_t>(items.size()), 0, qtiles[q0].req, 0};
       for (size_t q = q0; q < q1; ++q) {
         const QTile& t = qtiles[q];
         if (k >= t.n_ch) continue;
@@ -592,21 +625,31 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   std::vector<uint32_t> order(units.size());
   for (uint32_t i = 0; i < order.size(); ++i) order[i] = i;
   std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return units[a].weight > units[b].weight; });
-  std::vector<racer::AttnWork> die_list[racer::kXcds];
-  uint64_t die_load[racer::kXcds] = {};
-  for (uint32_t ui : order)
+  // (with a split: one set of die lists per run of requests, laid out one after the other)
+  const uint32_t n_runs = b_split ? 2 : 1;
+  std::vector<racer::AttnWork> die_list[2][racer::kXcds];
+  uint64_t die_load[2][racer::kXcds] = {};
+  for (uint32_t ui : order) {
+    const uint32_t run = b_split && units[ui].req >= b_split ? 1 : 0;
     for (uint32_t h = 0; h < c.H; ++h) {
       uint32_t best = 0;
       for (uint32_t x = 1; x < racer::kXcds; ++x)
-        if (die_load[x] < die_load[best]) best = x;
-      die_load[best] += units[ui].weight;
-      for (uint32_t i = 0; i < units[ui].n_items; ++i) die_list[best].push_back({units[ui].item0 + i, h});
+        if (die_load[run][x] < die_load[run][best]) best = x;
+      die_load[run][best] += units[ui].weight;
+      for (uint32_t i = 0; i < units[ui].n_items; ++i) die_list[run][best].push_back({units[ui].item0 + i, h});
     }
-  size_t die_len = 0;
-  for (uint32_t x = 0; x < racer::kXcds; ++x) die_len = std::max(die_len, die_list[x].size());
-  std::vector<racer::AttnWork> work(die_len * racer::kXcds, racer::AttnWork{racer::kNoWork, 0});
-  for (uint32_t x = 0; x < racer::kXcds; ++x)
-    for (size_t i = 0; i < die_list[x].size(); ++i) work[i * racer::kXcds + x] = die_list[x][i];
+  }
+  std::vector<racer::AttnWork> work;
+  size_t work_begin[3] = {0, 0, 0};
+  for (uint32_t run = 0; run < n_runs; ++run) {
+    size_t die_len = 0;
+    for (uint32_t x = 0; x < racer::kXcds; ++x) die_len = std::max(die_len, die_list[run][x].size());
+    work_begin[run] = work.size();
+    work.resize(work.size() + die_len * racer::kXcds, racer::AttnWork{racer::kNoWork, 0});
+    for (uint32_t x = 0; x < racer::kXcds; ++x)
+      for (size_t i = 0; i < die_list[run][x].size(); ++i) work[work_begin[run] + i * racer::kXcds + x] = die_list[run][x][i];
+  }
+  work_begin[n_runs] = work.size();
   const uint64_t partial_bytes = static_cast<uint64_t>(n_slots) * c.H * q_block * 64 * sizeof(float);
   if (partial_bytes > p->hp_cap) {
     HIP_TRY(hipStreamSynchronize(p->last_stream));
@@ -679,6 +722,23 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   ctx->sl.n_row_tiles = static_cast<uint32_t>(row_tiles.size());
   ctx->sl.B = B;
   ctx->sl.N = static_cast<uint32_t>(N);
+  ctx->b_split = b_split;
+  if (b_split) {
+    // groups and row tiles were built request after request: the first run's are a prefix of each array
+    size_t g0 = 0, t0 = 0;
+    while (g0 < groups.size() && groups[g0].req < b_split) ++g0;
+    while (t0 < row_tiles.size() && row_tiles[t0].req < b_split) ++t0;
+    for (uint32_t run = 0; run < 2; ++run) {
+      racer::StepLists& h = ctx->half[run];
+      h = ctx->sl;
+      h.work = ctx->sl.work + work_begin[run];
+      h.n_work = static_cast<uint32_t>(work_begin[run + 1] - work_begin[run]);
+      h.groups = ctx->sl.groups + (run ? g0 : 0);
+      h.n_groups = static_cast<uint32_t>(run ? groups.size() - g0 : g0);
+      h.row_tiles = ctx->sl.row_tiles + (run ? t0 : 0);
+      h.n_row_tiles = static_cast<uint32_t>(run ? row_tiles.size() - t0 : t0);
+    }
+  }
   return RACER_OK;
 }
 
@@ -706,14 +766,21 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
                   uint64_t n_page_entries, const void* x_in, const int64_t* ts, void* out, void* stream_v) {
   if (!p || !m || (B && !reqs)) return RACER_EINVAL;
   hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  const racer_hstu_cfg& c = m->cfg;
+  // A large bf16 batch runs as two pipelines, one per run of requests, the second on a stream of the pool's own:
+  // requests share nothing inside a step, and the workgroups of one pipeline's kernel fill the slots that the
+  // other's leaves idle towards its end.  Not while kernels are being timed (their durations would overlap).
+  const bool fused = c.elem == RACER_ELEM_BF16 && (c.d == 128 || c.d == 256);
+  uint64_t n_tokens = 0;
+  for (uint32_t r = 0; r < B; ++r) n_tokens += reqs[r].new_len;
+  const bool want_split = fused && !p->prof_on && B >= 2 && n_tokens >= kSplitMinTokens;
   StepCtx ctx;
-  int32_t rc = prepare_step(p, m, reqs, B, n_page_entries, stream, &ctx);
+  int32_t rc = prepare_step(p, m, reqs, B, n_page_entries, stream, &ctx, want_split);
   if (rc) return rc;
   p->last_stream = stream;
   const uint32_t N = ctx.sl.N;
   if (N == 0) return RACER_OK;
   if (!page_tables || !x_in || !ts || !out) return RACER_EINVAL;
-  const racer_hstu_cfg& c = m->cfg;
   const uint64_t d = c.d;
   if ((rc = ensure_hstu_ws(p, N, d, ctx.esize, stream))) return rc;
   const uint64_t stride = ((static_cast<uint64_t>(p->hw_rows) * d * ctx.esize) + 255) & ~255ull;
@@ -724,9 +791,20 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
   uint8_t* xb[2] = {o + stride, o + 2 * stride};
   const bool bf16 = c.elem == RACER_ELEM_BF16;
   const uint64_t w1_layer = d * 4 * d * ctx.esize, w2_layer = d * d * ctx.esize;
-  const void* x_cur = x_in;
-  for (uint32_t l = 0; l < c.L; ++l) {
-    void* x_next = (l + 1 == c.L) ? out : static_cast<void*>(xb[l & 1]);
+  bool split = ctx.b_split != 0;
+  for (int run = 0; split && run < 2; ++run)
+    if (ctx.half[run].n_row_tiles == 0 || ctx.half[run].n_work == 0) split = false;  // a run without new tokens
+  if (split && !p->aux_stream) {
+    HIP_TRY(hipStreamCreateWithFlags(&p->aux_stream, hipStreamNonBlocking));
+    HIP_TRY(hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming));
+    HIP_TRY(hipEventCreateWithFlags(&p->ev_join, hipEventDisableTiming));
+  }
+  if (split) {  // the second pipeline starts behind everything the caller's stream holds so far (lists included)
+    HIP_TRY(hipEventRecord(p->ev_fork, stream));
+    HIP_TRY(hipStreamWaitEvent(p->aux_stream, p->ev_fork, 0));
+  }
+  // one layer of one pipeline: rows, pages and partial slots of `sl` only
+  auto layer_of = [&](const racer::StepLists& sl, hipStream_t st, uint32_t l, const void* x_cur, void* x_next) -> int32_t {
     const float* ln1_g = static_cast<const float*>(m->w.ln1_g) + l * d;
     const float* ln1_b = static_cast<const float*>(m->w.ln1_b) + l * d;
     const float* ln2_g = static_cast<const float*>(m->w.ln2_g) + l * d;
@@ -735,40 +813,54 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
     const float* b2 = static_cast<const float*>(m->w.b2) + l * d;
     const uint8_t* w1 = static_cast<const uint8_t*>(bf16 ? m->w1t : m->w.w1) + l * w1_layer;
     const uint8_t* w2 = static_cast<const uint8_t*>(bf16 ? m->w2t : m->w.w2) + l * w2_layer;
-    const bool fused = racer::layer_halves_fused(ctx.hd);
     if (fused) {
-      ProfScope t(p, RACER_PROF_GEMM_FRONT, stream);
-      HIP_TRY(racer::launch_layer_front_fused(ctx.hd, l, x_cur, ln1_g, ln1_b, w1, b1, u, q, ctx.kv, ctx.sl, page_tables, stream));
+      ProfScope t(p, RACER_PROF_GEMM_FRONT, st);
+      HIP_TRY(racer::launch_layer_front_fused(ctx.hd, l, x_cur, ln1_g, ln1_b, w1, b1, u, q, ctx.kv, sl, page_tables, st));
     } else {
       {
-        ProfScope t(p, RACER_PROF_LAYERNORM, stream);
-        HIP_TRY(racer::launch_layernorm(ctx.hd, x_cur, ln1_g, ln1_b, nullptr, xn, N, stream));
+        ProfScope t(p, RACER_PROF_LAYERNORM, st);
+        HIP_TRY(racer::launch_layernorm(ctx.hd, x_cur, ln1_g, ln1_b, nullptr, xn, N, st));
       }
-      ProfScope t(p, RACER_PROF_GEMM_FRONT, stream);
-      HIP_TRY(racer::launch_gemm_front(ctx.hd, l, xn, w1, b1, u, q, ctx.kv, ctx.sl, page_tables, stream));
+      ProfScope t(p, RACER_PROF_GEMM_FRONT, st);
+      HIP_TRY(racer::launch_gemm_front(ctx.hd, l, xn, w1, b1, u, q, ctx.kv, sl, page_tables, st));
     }
     {
-      ProfScope t(p, RACER_PROF_ATTENTION, stream);
+      ProfScope t(p, RACER_PROF_ATTENTION, st);
       HIP_TRY(racer::launch_attention(ctx.hd, l, q, bf16 ? m->pos_s : static_cast<const float*>(m->w.pos),
-                                      bf16 ? m->time_s : static_cast<const float*>(m->w.time), ctx.kv, ctx.sl,
-                                      page_tables, ts, o, stream));
+                                      bf16 ? m->time_s : static_cast<const float*>(m->w.time), ctx.kv, sl,
+                                      page_tables, ts, o, st));
     }
-    if (ctx.sl.n_groups) {
-      ProfScope t(p, RACER_PROF_ATTN_REDUCE, stream);
-      HIP_TRY(racer::launch_attention_reduce(ctx.hd, ctx.sl, o, stream));
+    if (sl.n_groups) {
+      ProfScope t(p, RACER_PROF_ATTN_REDUCE, st);
+      HIP_TRY(racer::launch_attention_reduce(ctx.hd, sl, o, st));
     }
     if (fused) {
-      ProfScope t(p, RACER_PROF_GEMM_BACK, stream);
-      HIP_TRY(racer::launch_layer_back_fused(ctx.hd, o, u, ln2_g, ln2_b, w2, b2, x_cur, x_next, ctx.sl, stream));
+      ProfScope t(p, RACER_PROF_GEMM_BACK, st);
+      HIP_TRY(racer::launch_layer_back_fused(ctx.hd, o, u, ln2_g, ln2_b, w2, b2, x_cur, x_next, sl, st));
     } else {
       {
-        ProfScope t(p, RACER_PROF_LAYERNORM, stream);
-        HIP_TRY(racer::launch_layernorm(ctx.hd, o, ln2_g, ln2_b, u, xn, N, stream));
+        ProfScope t(p, RACER_PROF_LAYERNORM, st);
+        HIP_TRY(racer::launch_layernorm(ctx.hd, o, ln2_g, ln2_b, u, xn, N, st));
       }
-      ProfScope t(p, RACER_PROF_GEMM_BACK, stream);
-      HIP_TRY(racer::launch_gemm_back(ctx.hd, xn, w2, b2, x_cur, x_next, N, stream));
+      ProfScope t(p, RACER_PROF_GEMM_BACK, st);
+      HIP_TRY(racer::launch_gemm_back(ctx.hd, xn, w2, b2, x_cur, x_next, N, st));
+    }
+    return RACER_OK;
+  };
+  const void* x_cur = x_in;
+  for (uint32_t l = 0; l < c.L; ++l) {
+    void* x_next = (l + 1 == c.L) ? out : static_cast<void*>(xb[l & 1]);
+    if (split) {
+      if ((rc = layer_of(ctx.half[0], stream, l, x_cur, x_next))) return rc;
+      if ((rc = layer_of(ctx.half[1], p->aux_stream, l, x_cur, x_next))) return rc;
+    } else {
+      if ((rc = layer_of(ctx.sl, stream, l, x_cur, x_next))) return rc;
     }
     x_cur = x_next;
+  }
+  if (split) {  // the caller's stream goes on when both pipelines are through
+    HIP_TRY(hipEventRecord(p->ev_join, p->aux_stream));
+    HIP_TRY(hipStreamWaitEvent(stream, p->ev_join, 0));
   }
   return RACER_OK;
 }

@@ -243,3 +243,31 @@ def test_shape_errors_are_reported():
     assert rc == B.EINVAL
     other.close()
     c.close()
+
+
+def test_two_pipeline_step_equals_the_single_pipeline_step_bit_for_bit():
+    # A batch of 32 768 or more new tokens runs as two pipelines on two streams, unless kernels are being timed.
+    # Same work items, same chunking, same summation order: the outputs and the stored K,V must be identical,
+    # also when further work is queued on the caller's stream right behind the step.  (Parity of the two-pipeline
+    # step with the oracle: the full-size Mid test in test_gpu_configs.py.)
+    c = Case(31, 2, 128, 2, 64, True, 4096, 16, 4096.0, 1024)
+    lens = [3000, 1700, 4096, 2500, 64, 3900, 2048, 3333, 2900, 4000, 1500, 3800, 1]  # 34 837 tokens
+    reqs, pts, ts, x = c.inputs([0] * len(lens), lens)
+    xd = torch.from_numpy(x).to(Hn.DEV).to(torch.bfloat16)
+    ptd, tsd = torch.from_numpy(pts).to(Hn.DEV), torch.from_numpy(ts).to(Hn.DEV)
+    outs, kvs = [], []
+    for timed in (0, 1, 0):
+        c.pool.mem.zero_()
+        B.racer_prof_enable(c.pool.h, timed)
+        out = torch.empty_like(xd)
+        assert B.hstu_step(c.pool.h, c.model.h, reqs, ptd, xd, tsd, out) == B.OK, B.last_error()
+        follow = out.float().sum(dim=1)  # queued behind the step on the same stream: must see the finished output
+        torch.cuda.synchronize()
+        assert torch.equal(follow, out.float().sum(dim=1))
+        outs.append(out.clone())
+        kvs.append(c.pool.mem.clone())
+    B.racer_prof_enable(c.pool.h, 0)
+    assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
+    assert torch.equal(outs[0].view(torch.int16), outs[2].view(torch.int16))
+    assert torch.equal(kvs[0], kvs[1]) and torch.equal(kvs[0], kvs[2])
+    c.close()
