@@ -194,9 +194,9 @@ int32_t hstu_model_destroy(racer_hstu_t* model);
  * to positions 0..its own through the page table.  Page ids outside the pool are skipped
  * and counted in bad_pages.  The work is ordered on `stream` as usual: what the caller
  * queues behind the call sees the finished outputs.  Inside, a bf16 batch of 32 768 or more
- * new tokens (d = 128 or 256) runs as two pipelines over two runs of requests, the second
- * on a stream of the pool's own (default priority) that forks from `stream` at the start
- * and joins it at the end; results do not depend on it.  While racer_prof_enable is on,
+ * new tokens (d = 128 or 256) runs as three pipelines over three runs of requests, two of
+ * them on streams of the pool's own (default priority) that fork from `stream` at the start
+ * and join it at the end; results do not depend on it.  While racer_prof_enable is on,
  * the step runs as one pipeline so that kernel durations do not overlap.
  * Errors: RACER_EINVAL (shape mismatch with the pool, offsets beyond n_page_entries),
  * RACER_ENOMEM/RACER_EHIP (workspace). */

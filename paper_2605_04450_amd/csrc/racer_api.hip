@@ -116,9 +116,9 @@ struct racer_pool {
   uint64_t hp_cap = 0;  // fp32 partial outputs of split attention items
   uint8_t* hp_dev = nullptr;
   Staging hstage;
-  // second stream of a step that runs as two pipelines (default priority), with its fork and join events
-  hipStream_t aux_stream = nullptr;
-  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  // further streams of a step that runs as several pipelines (default priority), with the fork and join events
+  hipStream_t aux_stream[3] = {nullptr, nullptr, nullptr};
+  hipEvent_t ev_fork = nullptr, ev_join[3] = {nullptr, nullptr, nullptr};
   // optional per-kernel-class timing with events on the caller's stream
   struct ProfMark { hipEvent_t a, b; int kind; };
   bool prof_on = false;
@@ -295,12 +295,13 @@ int32_t pool_destroy(racer_pool_t* p) {
       (void)hipEventDestroy(m.b);
     }
     for (hipEvent_t e : p->prof_spare) (void)hipEventDestroy(e);
-    if (p->aux_stream) {
-      (void)hipStreamSynchronize(p->aux_stream);
-      (void)hipStreamDestroy(p->aux_stream);
-      (void)hipEventDestroy(p->ev_fork);
-      (void)hipEventDestroy(p->ev_join);
-    }
+    for (int k = 0; k < 3; ++k)
+      if (p->aux_stream[k]) {
+        (void)hipStreamSynchronize(p->aux_stream[k]);
+        (void)hipStreamDestroy(p->aux_stream[k]);
+        (void)hipEventDestroy(p->ev_join[k]);
+      }
+    if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
     (void)hipFree(p->d_tags);
     (void)hipFree(p->d_stamps);
     (void)hipFree(p->d_emb_pages);
@@ -518,20 +519,26 @@ namespace {
 #define RACER_SPLIT_MIN_TOKENS 32768
 #endif
 constexpr uint64_t kSplitMinTokens = RACER_SPLIT_MIN_TOKENS;
+#ifndef RACER_STEP_RUNS
+#define RACER_STEP_RUNS 3
+#endif
+constexpr uint32_t kMaxRuns = 4;
+constexpr uint32_t kStepRuns = RACER_STEP_RUNS;  // pipelines of a large step
+static_assert(kStepRuns >= 2 && kStepRuns <= kMaxRuns, "pipelines per step");
 
 struct StepCtx {
   racer::HstuDims hd;
   racer::KvView kv;
   racer::StepLists sl;       // the whole batch
-  racer::StepLists half[2];  // with a split: requests [0, b_split) and [b_split, B), each with lists of its own
-  uint32_t b_split = 0;      // 0: no split
+  racer::StepLists run[kMaxRuns];  // with a split: consecutive runs of requests, each with lists of its own
+  uint32_t n_runs = 1;             // 1: no split
   uint64_t esize;
 };
 
 // Validate the requests, build the row->request map and the attention work lists, ship them
-// to the device on `stream`.  With `want_split` the batch is also cut into two runs of requests with about
-// equal attention work, each with its own work list, groups and row tiles (two pipelines that touch disjoint
-// rows, pages and partial slots), if it has at least two requests.
+// to the device on `stream`.  With `want_split` the batch is also cut into kStepRuns runs of requests with about
+// equal attention work, each with its own work list, groups and row tiles (pipelines that touch disjoint rows,
+// pages and partial slots), if it has at least as many requests as pipelines.
 int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, uint32_t B, uint64_t n_page_entries,
                      hipStream_t stream, StepCtx* ctx, bool want_split = false) {
   const racer_hstu_cfg& c = m->cfg;
@@ -568,20 +575,32 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
       visits += last / 64 + 1;
     }
   }
-  uint32_t b_split = 0;
-  if (want_split && B >= 2) {
-    // the cut that balances the visits of the two runs best
-    uint64_t acc = 0, best_diff = ~0ull;
+  // run_begin[k] = first request of run k; a cut is placed where the visits so far come closest to k / n_runs of all
+  uint32_t n_runs = 1, run_begin[kMaxRuns + 1] = {0, B, B, B, B};
+  if (want_split && B >= kStepRuns) {
+    n_runs = kStepRuns;
+    uint64_t acc = 0;
     size_t qi = 0;
-    for (uint32_t r = 0; r + 1 < B; ++r) {
+    uint32_t k = 1;
+    for (uint32_t r = 0; r < B && k < n_runs; ++r) {
+      const uint64_t before = acc;
       while (qi < qtiles.size() && qtiles[qi].req == r) acc += qtiles[qi++].n_kt;
-      const uint64_t diff = acc * 2 > visits ? acc * 2 - visits : visits - acc * 2;
-      if (diff < best_diff) {
-        best_diff = diff;
-        b_split = r + 1;
+      const uint64_t target = visits * k / n_runs;
+      if (acc >= target) {  // the cut goes before or after request r, whichever is closer; runs stay non-empty
+        uint32_t cut = (acc - target <= target - before) ? r + 1 : r;
+        cut = std::max(cut, run_begin[k - 1] + 1);
+        cut = std::min(cut, B - (n_runs - k));
+        run_begin[k++] = cut;
       }
     }
+    while (k < n_runs) { run_begin[k] = std::max(run_begin[k - 1] + 1, B - (n_runs - k)); ++k; }
+    run_begin[n_runs] = B;
   }
+  auto run_of = [&](uint32_t req) {
+    uint32_t k = 0;
+    while (k + 1 < n_runs && req >= run_begin[k + 1]) ++k;
+    return k;
+  };
   const uint64_t block_slots = 1024;  // about 256 CUs x resident blocks
   uint32_t chunk = static_cast<uint32_t>(std::max<uint64_t>(8, (visits * c.H + 2 * block_slots - 1) / (2 * block_slots)));
   // an item's slice of the page table (a chunk and a quarter at most) must fit the kernel's LDS copy
@@ -626,11 +645,10 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   for (uint32_t i = 0; i < order.size(); ++i) order[i] = i;
   std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return units[a].weight > units[b].weight; });
   // (with a split: one set of die lists per run of requests, laid out one after the other)
-  const uint32_t n_runs = b_split ? 2 : 1;
-  std::vector<racer::AttnWork> die_list[2][racer::kXcds];
-  uint64_t die_load[2][racer::kXcds] = {};
+  std::vector<racer::AttnWork> die_list[kMaxRuns][racer::kXcds];
+  uint64_t die_load[kMaxRuns][racer::kXcds] = {};
   for (uint32_t ui : order) {
-    const uint32_t run = b_split && units[ui].req >= b_split ? 1 : 0;
+    const uint32_t run = run_of(units[ui].req);
     for (uint32_t h = 0; h < c.H; ++h) {
       uint32_t best = 0;
       for (uint32_t x = 1; x < racer::kXcds; ++x)
@@ -640,7 +658,7 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
     }
   }
   std::vector<racer::AttnWork> work;
-  size_t work_begin[3] = {0, 0, 0};
+  size_t work_begin[kMaxRuns + 1] = {};
   for (uint32_t run = 0; run < n_runs; ++run) {
     size_t die_len = 0;
     for (uint32_t x = 0; x < racer::kXcds; ++x) die_len = std::max(die_len, die_list[run][x].size());
@@ -722,21 +740,22 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   ctx->sl.n_row_tiles = static_cast<uint32_t>(row_tiles.size());
   ctx->sl.B = B;
   ctx->sl.N = static_cast<uint32_t>(N);
-  ctx->b_split = b_split;
-  if (b_split) {
-    // groups and row tiles were built request after request: the first run's are a prefix of each array
-    size_t g0 = 0, t0 = 0;
-    while (g0 < groups.size() && groups[g0].req < b_split) ++g0;
-    while (t0 < row_tiles.size() && row_tiles[t0].req < b_split) ++t0;
-    for (uint32_t run = 0; run < 2; ++run) {
-      racer::StepLists& h = ctx->half[run];
+  ctx->n_runs = n_runs;
+  if (n_runs > 1) {
+    // groups and row tiles were built request after request: a run's are a contiguous piece of each array
+    size_t g = 0, t = 0;
+    for (uint32_t run = 0; run < n_runs; ++run) {
+      racer::StepLists& h = ctx->run[run];
       h = ctx->sl;
       h.work = ctx->sl.work + work_begin[run];
       h.n_work = static_cast<uint32_t>(work_begin[run + 1] - work_begin[run]);
-      h.groups = ctx->sl.groups + (run ? g0 : 0);
-      h.n_groups = static_cast<uint32_t>(run ? groups.size() - g0 : g0);
-      h.row_tiles = ctx->sl.row_tiles + (run ? t0 : 0);
-      h.n_row_tiles = static_cast<uint32_t>(run ? row_tiles.size() - t0 : t0);
+      const size_t g0 = g, t0 = t;
+      while (g < groups.size() && groups[g].req < run_begin[run + 1]) ++g;
+      while (t < row_tiles.size() && row_tiles[t].req < run_begin[run + 1]) ++t;
+      h.groups = ctx->sl.groups + g0;
+      h.n_groups = static_cast<uint32_t>(g - g0);
+      h.row_tiles = ctx->sl.row_tiles + t0;
+      h.n_row_tiles = static_cast<uint32_t>(t - t0);
     }
   }
   return RACER_OK;
@@ -767,9 +786,9 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
   if (!p || !m || (B && !reqs)) return RACER_EINVAL;
   hipStream_t stream = static_cast<hipStream_t>(stream_v);
   const racer_hstu_cfg& c = m->cfg;
-  // A large bf16 batch runs as two pipelines, one per run of requests, the second on a stream of the pool's own:
-  // requests share nothing inside a step, and the workgroups of one pipeline's kernel fill the slots that the
-  // other's leaves idle towards its end.  Not while kernels are being timed (their durations would overlap).
+  // A large bf16 batch runs as several pipelines, one per run of requests, all but the first on streams of the
+  // pool's own: requests share nothing inside a step, and the workgroups of one pipeline's kernel fill the slots
+  // that another's leaves idle towards its end.  Not while kernels are being timed (their durations would overlap).
   const bool fused = c.elem == RACER_ELEM_BF16 && (c.d == 128 || c.d == 256);
   uint64_t n_tokens = 0;
   for (uint32_t r = 0; r < B; ++r) n_tokens += reqs[r].new_len;
@@ -791,17 +810,20 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
   uint8_t* xb[2] = {o + stride, o + 2 * stride};
   const bool bf16 = c.elem == RACER_ELEM_BF16;
   const uint64_t w1_layer = d * 4 * d * ctx.esize, w2_layer = d * d * ctx.esize;
-  bool split = ctx.b_split != 0;
-  for (int run = 0; split && run < 2; ++run)
-    if (ctx.half[run].n_row_tiles == 0 || ctx.half[run].n_work == 0) split = false;  // a run without new tokens
-  if (split && !p->aux_stream) {
-    HIP_TRY(hipStreamCreateWithFlags(&p->aux_stream, hipStreamNonBlocking));
-    HIP_TRY(hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming));
-    HIP_TRY(hipEventCreateWithFlags(&p->ev_join, hipEventDisableTiming));
-  }
-  if (split) {  // the second pipeline starts behind everything the caller's stream holds so far (lists included)
+  const uint32_t n_runs = ctx.n_runs;
+  bool split = n_runs > 1;
+  for (uint32_t run = 0; split && run < n_runs; ++run)
+    if (ctx.run[run].n_row_tiles == 0 || ctx.run[run].n_work == 0) split = false;  // a run without new tokens
+  if (split) {  // the other pipelines start behind everything the caller's stream holds so far (lists included)
+    if (!p->ev_fork) HIP_TRY(hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming));
     HIP_TRY(hipEventRecord(p->ev_fork, stream));
-    HIP_TRY(hipStreamWaitEvent(p->aux_stream, p->ev_fork, 0));
+    for (uint32_t k = 0; k + 1 < n_runs; ++k) {
+      if (!p->aux_stream[k]) {
+        HIP_TRY(hipStreamCreateWithFlags(&p->aux_stream[k], hipStreamNonBlocking));
+        HIP_TRY(hipEventCreateWithFlags(&p->ev_join[k], hipEventDisableTiming));
+      }
+      HIP_TRY(hipStreamWaitEvent(p->aux_stream[k], p->ev_fork, 0));
+    }
   }
   // one layer of one pipeline: rows, pages and partial slots of `sl` only
   auto layer_of = [&](const racer::StepLists& sl, hipStream_t st, uint32_t l, const void* x_cur, void* x_next) -> int32_t {
@@ -851,16 +873,18 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
   for (uint32_t l = 0; l < c.L; ++l) {
     void* x_next = (l + 1 == c.L) ? out : static_cast<void*>(xb[l & 1]);
     if (split) {
-      if ((rc = layer_of(ctx.half[0], stream, l, x_cur, x_next))) return rc;
-      if ((rc = layer_of(ctx.half[1], p->aux_stream, l, x_cur, x_next))) return rc;
+      for (uint32_t run = 0; run < n_runs; ++run)
+        if ((rc = layer_of(ctx.run[run], run ? p->aux_stream[run - 1] : stream, l, x_cur, x_next))) return rc;
     } else {
       if ((rc = layer_of(ctx.sl, stream, l, x_cur, x_next))) return rc;
     }
     x_cur = x_next;
   }
-  if (split) {  // the caller's stream goes on when both pipelines are through
-    HIP_TRY(hipEventRecord(p->ev_join, p->aux_stream));
-    HIP_TRY(hipStreamWaitEvent(stream, p->ev_join, 0));
+  if (split) {  // the caller's stream goes on when every pipeline is through
+    for (uint32_t k = 0; k + 1 < n_runs; ++k) {
+      HIP_TRY(hipEventRecord(p->ev_join[k], p->aux_stream[k]));
+      HIP_TRY(hipStreamWaitEvent(stream, p->ev_join[k], 0));
+    }
   }
   return RACER_OK;
 }
