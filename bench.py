@@ -706,6 +706,9 @@ def main():
     ap.add_argument("--config", default="mid", choices=sorted(CONFIGS))
     ap.add_argument("--cpu-tokens", type=int, default=None, help="token budget of the oracle sample")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--one-pipeline", action="store_true",
+                    help="run the throughput pass as one pipeline as well (per-kernel events on): every kernel launch "
+                         "then covers the whole batch, which is what a per-kernel profile of the run needs")
     ap.add_argument("--copy-calib-mb", type=int, default=0,
                     help="after the timed region, run one plain device copy of this many MiB (a kernel of known "
                          "traffic against which HBM byte counters of a profiler run are scaled)")
@@ -744,9 +747,12 @@ def main():
     # warm the EMB cache, then whole warm-up steps
     for k in range(c["warm_batches"]):
         B.emb_lookup(pool.h, wl["ids_dev"][k % 4], wl["x"], 1, None)
+    if args.one_pipeline:
+        B.racer_prof_enable(pool.h, 1)
     for k in range(args.warmup):
         one_step(wl, k, B)
     torch.cuda.synchronize()
+    B.racer_prof_read(pool.h)
     st0 = pool.stats()
     # the timed region: K whole steps, nothing but the library's own work on the stream
     torch.cuda.synchronize()
