@@ -194,7 +194,7 @@ int32_t hstu_model_destroy(racer_hstu_t* model);
  * to positions 0..its own through the page table.  Page ids outside the pool are skipped
  * and counted in bad_pages.  The work is ordered on `stream` as usual: what the caller
  * queues behind the call sees the finished outputs.  Inside, a bf16 batch of 32 768 or more
- * new tokens (d = 128 or 256) runs as three pipelines over three runs of requests, two of
+ * new tokens, or 2^26 or more (query, key) pairs, runs as three pipelines over three runs of requests, two of
  * them on streams of the pool's own (default priority) that fork from `stream` at the start
  * and join it at the end; results do not depend on it.  While racer_prof_enable is on,
  * the step runs as one pipeline so that kernel durations do not overlap.

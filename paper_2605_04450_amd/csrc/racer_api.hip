@@ -519,6 +519,11 @@ namespace {
 #define RACER_SPLIT_MIN_TOKENS 32768
 #endif
 constexpr uint64_t kSplitMinTokens = RACER_SPLIT_MIN_TOKENS;
+// ... or with fewer (query, key) pairs than this (a few new tokens against long cached prefixes are a large step too)
+#ifndef RACER_SPLIT_MIN_PAIRS
+#define RACER_SPLIT_MIN_PAIRS (64ull << 20)
+#endif
+constexpr uint64_t kSplitMinPairs = RACER_SPLIT_MIN_PAIRS;
 #ifndef RACER_STEP_RUNS
 #define RACER_STEP_RUNS 3
 #endif
@@ -531,6 +536,7 @@ struct StepCtx {
   racer::KvView kv;
   racer::StepLists sl;       // the whole batch
   racer::StepLists run[kMaxRuns];  // with a split: consecutive runs of requests, each with lists of its own
+  uint32_t run_row0[kMaxRuns] = {}, run_rows[kMaxRuns] = {};  // a run's new-token rows
   uint32_t n_runs = 1;             // 1: no split
   uint64_t esize;
 };
@@ -756,6 +762,9 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
       h.n_groups = static_cast<uint32_t>(g - g0);
       h.row_tiles = ctx->sl.row_tiles + t0;
       h.n_row_tiles = static_cast<uint32_t>(t - t0);
+      ctx->run_row0[run] = run_begin[run] < B ? static_cast<uint32_t>(reqs[run_begin[run]].x_off) : static_cast<uint32_t>(N);
+      const uint64_t row_end = run_begin[run + 1] < B ? reqs[run_begin[run + 1]].x_off : N;
+      ctx->run_rows[run] = static_cast<uint32_t>(row_end - ctx->run_row0[run]);
     }
   }
   return RACER_OK;
@@ -790,9 +799,13 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
   // pool's own: requests share nothing inside a step, and the workgroups of one pipeline's kernel fill the slots
   // that another's leaves idle towards its end.  Not while kernels are being timed (their durations would overlap).
   const bool fused = c.elem == RACER_ELEM_BF16 && (c.d == 128 || c.d == 256);
-  uint64_t n_tokens = 0;
-  for (uint32_t r = 0; r < B; ++r) n_tokens += reqs[r].new_len;
-  const bool want_split = fused && !p->prof_on && B >= 2 && n_tokens >= kSplitMinTokens;
+  uint64_t n_tokens = 0, n_pairs = 0;
+  for (uint32_t r = 0; r < B; ++r) {
+    n_tokens += reqs[r].new_len;
+    n_pairs += static_cast<uint64_t>(reqs[r].new_len) * (reqs[r].prefix_len + reqs[r].new_len / 2);
+  }
+  const bool want_split = c.elem == RACER_ELEM_BF16 && !p->prof_on && B >= 2 &&
+                          (n_tokens >= kSplitMinTokens || n_pairs >= kSplitMinPairs);
   StepCtx ctx;
   int32_t rc = prepare_step(p, m, reqs, B, n_page_entries, stream, &ctx, want_split);
   if (rc) return rc;
@@ -826,7 +839,12 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
     }
   }
   // one layer of one pipeline: rows, pages and partial slots of `sl` only
-  auto layer_of = [&](const racer::StepLists& sl, hipStream_t st, uint32_t l, const void* x_cur, void* x_next) -> int32_t {
+  auto layer_of = [&](const racer::StepLists& sl, uint32_t row0, uint32_t rows, hipStream_t st, uint32_t l,
+                      const void* x_cur, void* x_next) -> int32_t {
+    // the separate LayerNorm and output GEMM work on rows [row0, row0 + rows) of every matrix
+    const uint64_t off = static_cast<uint64_t>(row0) * d * ctx.esize;
+    auto at = [&](const void* base) { return static_cast<const uint8_t*>(base) + off; };
+    auto at_w = [&](void* base) { return static_cast<uint8_t*>(base) + off; };
     const float* ln1_g = static_cast<const float*>(m->w.ln1_g) + l * d;
     const float* ln1_b = static_cast<const float*>(m->w.ln1_b) + l * d;
     const float* ln2_g = static_cast<const float*>(m->w.ln2_g) + l * d;
@@ -841,7 +859,7 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
     } else {
       {
         ProfScope t(p, RACER_PROF_LAYERNORM, st);
-        HIP_TRY(racer::launch_layernorm(ctx.hd, x_cur, ln1_g, ln1_b, nullptr, xn, N, st));
+        HIP_TRY(racer::launch_layernorm(ctx.hd, at(x_cur), ln1_g, ln1_b, nullptr, at_w(xn), rows, st));
       }
       ProfScope t(p, RACER_PROF_GEMM_FRONT, st);
       HIP_TRY(racer::launch_gemm_front(ctx.hd, l, xn, w1, b1, u, q, ctx.kv, sl, page_tables, st));
@@ -862,10 +880,10 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
     } else {
       {
         ProfScope t(p, RACER_PROF_LAYERNORM, st);
-        HIP_TRY(racer::launch_layernorm(ctx.hd, o, ln2_g, ln2_b, u, xn, N, st));
+        HIP_TRY(racer::launch_layernorm(ctx.hd, at(o), ln2_g, ln2_b, at(u), at_w(xn), rows, st));
       }
       ProfScope t(p, RACER_PROF_GEMM_BACK, st);
-      HIP_TRY(racer::launch_gemm_back(ctx.hd, xn, w2, b2, x_cur, x_next, N, st));
+      HIP_TRY(racer::launch_gemm_back(ctx.hd, at(xn), w2, b2, at(x_cur), at_w(x_next), rows, st));
     }
     return RACER_OK;
   };
@@ -874,9 +892,11 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
     void* x_next = (l + 1 == c.L) ? out : static_cast<void*>(xb[l & 1]);
     if (split) {
       for (uint32_t run = 0; run < n_runs; ++run)
-        if ((rc = layer_of(ctx.run[run], run ? p->aux_stream[run - 1] : stream, l, x_cur, x_next))) return rc;
+        if ((rc = layer_of(ctx.run[run], ctx.run_row0[run], ctx.run_rows[run], run ? p->aux_stream[run - 1] : stream, l,
+                           x_cur, x_next)))
+          return rc;
     } else {
-      if ((rc = layer_of(ctx.sl, stream, l, x_cur, x_next))) return rc;
+      if ((rc = layer_of(ctx.sl, 0, N, stream, l, x_cur, x_next))) return rc;
     }
     x_cur = x_next;
   }

@@ -245,12 +245,13 @@ def test_shape_errors_are_reported():
     c.close()
 
 
-def test_pipelined_step_equals_the_single_pipeline_step_bit_for_bit():
+@pytest.mark.parametrize("L,d,H", [(2, 128, 2), (1, 512, 8)])  # fused layer halves; separate LayerNorm + GEMM kernels
+def test_pipelined_step_equals_the_single_pipeline_step_bit_for_bit(L, d, H):
     # A batch of 32 768 or more new tokens runs as three pipelines on three streams, unless kernels are being timed.
     # Same work items, same chunking, same summation order: the outputs and the stored K,V must be identical,
     # also when further work is queued on the caller's stream right behind the step.  (Parity of the pipelined
     # step with the oracle: the full-size Mid test in test_gpu_configs.py.)
-    c = Case(31, 2, 128, 2, 64, True, 4096, 16, 4096.0, 1024)
+    c = Case(31, L, d, H, 64, True, 4096, 16, 4096.0, 1024)
     lens = [3000, 1700, 4096, 2500, 64, 3900, 2048, 3333, 2900, 4000, 1500, 3800, 1]  # 34 837 tokens
     reqs, pts, ts, x = c.inputs([0] * len(lens), lens)
     xd = torch.from_numpy(x).to(Hn.DEV).to(torch.bfloat16)
