@@ -802,6 +802,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if c["bf16"] else "f32", "data": "synthetic",
         "ms_per_step_with_kernel_events": dt_events * 1e3 / args.steps,
+        "passes": {"throughput": "K steps as the library runs them (a batch of this size: three pipelines on three "
+                                 "streams)" if not args.one_pipeline else "K steps, one pipeline, kernel events on",
+                   "kernels": "the same K steps again as one pipeline with a HIP event before and after every kernel"},
         "config": {"workload": c["desc"], "new_tokens_per_step": int(N), "requests": int(c["batch"]),
                    "emb_frac": c["alpha"], "causal_pairs_per_layer": pairs},
         "emb_gather": {"GBps": gather_gbs, "frac_of_hbm_peak": gather_gbs / PEAK_HBM_GBS,
