@@ -245,14 +245,22 @@ def test_shape_errors_are_reported():
     c.close()
 
 
-@pytest.mark.parametrize("L,d,H", [(2, 128, 2), (1, 512, 8)])  # fused layer halves; separate LayerNorm + GEMM kernels
-def test_pipelined_step_equals_the_single_pipeline_step_bit_for_bit(L, d, H):
+MIXED = [3000, 1700, 4096, 2500, 64, 3900, 2048, 3333, 2900, 4000, 1500, 3800, 1]  # 34 837 tokens
+
+
+@pytest.mark.parametrize("L,d,H,lens", [
+    (2, 128, 2, MIXED),             # fused layer halves
+    (1, 512, 8, MIXED),             # separate LayerNorm + GEMM kernels
+    (1, 128, 2, [30000, 5, 3000]),  # one request holds nearly all the work: the cuts fall right behind it
+    (1, 128, 2, [20000, 15000]),    # fewer requests than pipelines: stays one pipeline
+    (1, 128, 2, [33000, 0, 0, 7]),  # requests without new tokens
+])
+def test_pipelined_step_equals_the_single_pipeline_step_bit_for_bit(L, d, H, lens):
     # A batch of 32 768 or more new tokens runs as three pipelines on three streams, unless kernels are being timed.
     # Same work items, same chunking, same summation order: the outputs and the stored K,V must be identical,
     # also when further work is queued on the caller's stream right behind the step.  (Parity of the pipelined
     # step with the oracle: the full-size Mid test in test_gpu_configs.py.)
     c = Case(31, L, d, H, 64, True, 4096, 16, 4096.0, 1024)
-    lens = [3000, 1700, 4096, 2500, 64, 3900, 2048, 3333, 2900, 4000, 1500, 3800, 1]  # 34 837 tokens
     reqs, pts, ts, x = c.inputs([0] * len(lens), lens)
     xd = torch.from_numpy(x).to(Hn.DEV).to(torch.bfloat16)
     ptd, tsd = torch.from_numpy(pts).to(Hn.DEV), torch.from_numpy(ts).to(Hn.DEV)
