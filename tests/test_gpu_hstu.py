@@ -280,3 +280,30 @@ def test_pipelined_step_equals_the_single_pipeline_step_bit_for_bit(L, d, H, len
     assert torch.equal(outs[0].view(torch.int16), outs[2].view(torch.int16))
     assert torch.equal(kvs[0], kvs[1]) and torch.equal(kvs[0], kvs[2])
     c.close()
+
+
+def test_pipelined_step_random_batches_match_the_single_pipeline():
+    # random request counts and lengths (total 33k-60k new tokens, so the pipelines are used), one pool reused
+    # from batch to batch without waiting in between
+    c = Case(77, 1, 128, 2, 64, True, 2048, 16, 2048.0, 2048)
+    rng = np.random.default_rng(5)
+    piped, serial = [], []
+    batches = []
+    for b in range(10):
+        n_req = int(rng.integers(3, 40))
+        lens = rng.integers(1, 3000, size=n_req)
+        lens = (lens * (rng.integers(33000, 60000) / lens.sum())).astype(np.int64) + 1
+        reqs, pts, ts, x = c.inputs([0] * n_req, lens.tolist())
+        batches.append((reqs, torch.from_numpy(pts).to(Hn.DEV), torch.from_numpy(ts).to(Hn.DEV),
+                        torch.from_numpy(x).to(Hn.DEV).to(torch.bfloat16)))
+    for timed, outs in ((0, piped), (1, serial)):
+        B.racer_prof_enable(c.pool.h, timed)
+        for reqs, ptd, tsd, xd in batches:  # back to back: the next step's lists and kernels queue behind this one
+            out = torch.empty_like(xd)
+            assert B.hstu_step(c.pool.h, c.model.h, reqs, ptd, xd, tsd, out) == B.OK, B.last_error()
+            outs.append(out)
+        torch.cuda.synchronize()
+    B.racer_prof_enable(c.pool.h, 0)
+    for k, (a, b_) in enumerate(zip(piped, serial)):
+        assert torch.equal(a.view(torch.int16), b_.view(torch.int16)), k
+    c.close()
