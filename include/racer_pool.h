@@ -137,6 +137,26 @@ int32_t kv_seq_release(racer_pool_t* pool, uint64_t key); /* RACER_EBUSY while p
 int32_t emb_lookup(racer_pool_t* pool, const int64_t* ids, uint64_t n, uint32_t bag, void* out,
                    uint8_t* hit_flags, void* stream);
 
+/* ---- several tables in one pool (paper Sec. II-B / III: a model looks up 10-25 embedding
+ *      tables per request, and the lookup cost grows linearly with their number) -----------
+ * pool_add_table: another pinned, device-mapped host table [rows][row_bytes] of the pool's
+ * element type behind the same hot cache; row_bytes a multiple of 16, at most the pool's
+ * (a narrower row occupies a whole slot, zero-padded).  Tables are numbered in the order
+ * they were added, pool_create's being table 0; *table_out (host, may be NULL) receives the
+ * number.  A row's global id is the sum of the rows of the tables before its own plus its
+ * row number: global ids are what the cache tags hold and what emb_lookup / emb_refill
+ * take once there is more than one table; all tables together must stay below 2^32 - 1
+ * rows, and there are at most 32.  Waits for the pool's stream.
+ * emb_lookup_tables: emb_lookup for (table, row) pairs: table_of (dev) u32[n], ids (dev)
+ * int64[n] row numbers inside their tables; all tables are probed in one launch.  out (dev)
+ * [n/bag][pool row_bytes]: a narrower table's row comes zero-padded.  A pair whose table or
+ * row does not exist counts as an invalid id.  Equal to emb_lookup on the concatenation of
+ * the zero-padded tables.  Errors: RACER_EINVAL (fewer than two tables, geometry), RACER_EHIP. */
+int32_t pool_add_table(racer_pool_t* pool, const void* host_table, uint64_t rows, uint32_t row_bytes,
+                       uint32_t* table_out);
+int32_t emb_lookup_tables(racer_pool_t* pool, const uint32_t* table_of, const int64_t* ids, uint64_t n,
+                          uint32_t bag, void* out, uint8_t* hit_flags, void* stream);
+
 /* ---- emb_refill (paper Sec. IV-B, last paragraph: after the EMB side has grown, its new
  *      capacity is filled with hot rows in the background, throttled against the live
  *      misses' host-to-device traffic) ------------------------------------------------------

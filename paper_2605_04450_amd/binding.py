@@ -19,7 +19,7 @@ TAG_EMPTY = 0xFFFFFFFF
 EXPORTS = [
     "pool_create", "pool_destroy", "pool_set_split", "pool_stats", "pool_dump", "emb_cache_dump",
     "pool_num_sets", "pool_slot_of", "kv_seq_reserve", "kv_seq_lookup", "kv_seq_pin", "kv_seq_unpin",
-    "kv_seq_release", "emb_lookup", "emb_refill", "hstu_model_create", "hstu_model_destroy", "hstu_step",
+    "kv_seq_release", "emb_lookup", "emb_refill", "pool_add_table", "emb_lookup_tables", "hstu_model_create", "hstu_model_destroy", "hstu_step",
     "hstu_attn_paged", "racer_last_error", "racer_prof_enable", "racer_prof_read",
 ]
 PROF_KINDS = ("emb_gather", "emb_miss", "layernorm", "gemm_front", "attention", "gemm_back", "attn_reduce")
@@ -89,6 +89,8 @@ def load():
         f.argtypes = [vp, u64]
     L.emb_lookup.argtypes = [vp, vp, u64, u32, vp, vp, vp]
     L.emb_refill.argtypes = [vp, vp, u64, vp]
+    L.pool_add_table.argtypes = [vp, vp, u64, u32, C.POINTER(u32)]
+    L.emb_lookup_tables.argtypes = [vp, vp, vp, u64, u32, vp, vp, vp]
     L.hstu_model_create.argtypes = [C.POINTER(HstuCfg), C.POINTER(HstuWeights), C.POINTER(vp)]
     L.hstu_model_destroy.argtypes = [vp]
     L.hstu_step.argtypes = [vp, vp, C.POINTER(HstuReq), u32, vp, u64, vp, vp, vp, vp]
@@ -225,6 +227,19 @@ def kv_seq_release(pool, key):
 def emb_lookup(pool, ids, out, bag=1, hit_flags=None, stream=None):
     """ids: int64 device tensor [n]; out: device tensor [n/bag][d]; hit_flags: uint8 device tensor [n] or None."""
     return load().emb_lookup(pool, _dp(ids), ids.numel(), bag, _dp(out), _dp(hit_flags), _stream_ptr(stream))
+
+
+def pool_add_table(pool, host_table, rows, row_bytes):
+    """host_table: pinned host tensor [rows][row_bytes / element size]. Returns (rc, table number)."""
+    t = C.c_uint32(0)
+    rc = load().pool_add_table(pool, _dp(host_table), rows, row_bytes, C.byref(t))
+    return rc, t.value
+
+
+def emb_lookup_tables(pool, table_of, ids, out, bag=1, hit_flags=None, stream=None):
+    """table_of: int32/uint32 device tensor [n]; ids: int64 device tensor [n] (rows inside their tables)."""
+    return load().emb_lookup_tables(pool, _dp(table_of), _dp(ids), ids.numel(), bag, _dp(out), _dp(hit_flags),
+                                    _stream_ptr(stream))
 
 
 def emb_refill(pool, ids, stream=None):

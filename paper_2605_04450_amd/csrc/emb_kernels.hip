@@ -669,9 +669,16 @@ __global__ __launch_bounds__(256) void miss_apply_fetch(EmbView v, MissWs ws, ui
       }
     }
     const uint8_t* src = v.table + static_cast<uint64_t>(id32) * v.row_bytes;
+    uint32_t src_chunks = chunks;
+    if (v.n_tables > 1) {  // the table whose range holds the id; its row may be narrower than a slot
+      uint32_t t = 0;
+      while (t + 1 < v.n_tables && v.tables[t + 1].base <= id32) ++t;
+      src = v.tables[t].ptr + (id32 - v.tables[t].base) * v.tables[t].row_bytes;
+      src_chunks = v.tables[t].row_bytes / 16;
+    }
     uint8_t* stg = ws.staging + static_cast<uint64_t>(u) * v.row_bytes;
     for (uint32_t c = l32; c < chunks; c += 32) {
-      const uint4 val = *reinterpret_cast<const uint4*>(src + 16 * c);
+      const uint4 val = c < src_chunks ? *reinterpret_cast<const uint4*>(src + 16 * c) : make_uint4(0, 0, 0, 0);
       if (!refill) *reinterpret_cast<uint4*>(stg + 16 * c) = val;
       if (dst) *reinterpret_cast<uint4*>(dst + 16 * c) = val;
     }
@@ -806,6 +813,19 @@ __global__ __launch_bounds__(256) void emb_shrink_sets(EmbView v, uint32_t old_f
   }
 }
 
+// (table, row) pairs -> global ids of the rows; -1 where the table or the row does not exist
+__global__ void emb_global_ids(EmbView v, const uint32_t* __restrict__ table_of, const int64_t* __restrict__ ids,
+                               uint32_t n, int64_t* __restrict__ gids) {
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    const uint32_t t = table_of[i];
+    const int64_t id = ids[i];
+    int64_t gid = -1;
+    if (t < v.n_tables && id >= 0 && static_cast<uint64_t>(id) < v.tables[t].rows)
+      gid = static_cast<int64_t>(v.tables[t].base) + id;
+    gids[i] = gid;
+  }
+}
+
 __global__ void fill_u32_kernel(uint32_t* p, uint64_t n, uint32_t value) {
   for (uint64_t k = blockIdx.x * static_cast<uint64_t>(blockDim.x) + threadIdx.x; k < n;
        k += static_cast<uint64_t>(gridDim.x) * blockDim.x)
@@ -865,6 +885,14 @@ hipError_t launch_emb_miss_path(const EmbView& v, const MissWs& ws, const int64_
   hipLaunchKernelGGL(miss_resolve, dim3(mblocks), dim3(256), 0, stream, ws, ids, batch);
   hipLaunchKernelGGL(miss_apply_fetch, dim3(mblocks), dim3(256), 0, stream, v, ws, batch, false);
   hipLaunchKernelGGL(emb_deferred_gather, dim3(mblocks), dim3(256), 0, stream, v, ws, bag, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_emb_global_ids(const EmbView& v, const uint32_t* table_of, const int64_t* ids, uint32_t n, int64_t* gids,
+                                 hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  const uint32_t blocks = n / 256 + 1 < 2048 ? n / 256 + 1 : 2048;
+  hipLaunchKernelGGL(emb_global_ids, dim3(blocks), dim3(256), 0, stream, v, table_of, ids, n, gids);
   return hipGetLastError();
 }
 

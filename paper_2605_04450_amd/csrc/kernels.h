@@ -19,6 +19,15 @@ constexpr int kCtrShards = 64;
 __device__ __forceinline__ int ctr_index(int counter) { return static_cast<int>(blockIdx.x & (kCtrShards - 1)) * kCtrCount + counter; }
 #endif
 
+// One embedding table behind the pool.  With several tables a row is known by its global id, base + row; rows
+// narrower than the pool's slots are kept zero-padded.
+struct TableDesc {
+  uint64_t base, rows;
+  const uint8_t* ptr;  // device-visible address of the pinned host rows
+  uint32_t row_bytes, pad;
+};
+constexpr uint32_t kMaxTables = 32;
+
 // Everything a kernel needs to find a cache set, its ways and its rows.
 // Way layer w of the cache = slot w of every set = `layer_pages` consecutive logical EMB
 // pages; slot (w, s) lives in logical page w*layer_pages + s/spp at offset s%spp.
@@ -37,7 +46,9 @@ struct EmbView {
   uint32_t* stamps;         // [sets][w_max]
   const int32_t* emb_pages; // logical -> physical page
   const uint8_t* table;     // device-visible address of the pinned host table
-  uint64_t rows;
+  uint64_t rows;            // rows of all tables together
+  const TableDesc* tables;  // more than one table: their descriptors, bases ascending (else nullptr)
+  uint32_t n_tables;
   unsigned long long* counters;
 };
 
@@ -76,6 +87,10 @@ hipError_t launch_emb_shrink(const EmbView& v, uint32_t old_full, uint32_t old_p
                              hipStream_t stream);
 
 hipError_t launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t stream);
+
+// (table, row) pairs -> global ids (-1 for a table or row that does not exist)
+hipError_t launch_emb_global_ids(const EmbView& v, const uint32_t* table_of, const int64_t* ids, uint32_t n, int64_t* gids,
+                                 hipStream_t stream);
 
 // ---- HSTU -----------------------------------------------------------------------------
 struct HstuDims {

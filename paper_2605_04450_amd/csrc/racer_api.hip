@@ -100,6 +100,11 @@ struct racer_pool {
   int32_t* d_emb_pages = nullptr;
   unsigned long long* d_counters = nullptr;
   const uint8_t* d_table = nullptr;
+  // every table behind the pool (the first is pool_create's); the device copy exists once a second one was added
+  std::vector<racer::TableDesc> tables;
+  racer::TableDesc* d_tables = nullptr;
+  int64_t* gid_buf = nullptr;  // global ids of a multi-table lookup
+  uint64_t gid_cap = 0;
   Staging stage;
   uint32_t batch = 0;
   uint64_t launches = 0;  // emb_lookup calls that reached the device (selects the list-counter parity)
@@ -143,7 +148,9 @@ struct racer_pool {
     v.stamps = d_stamps;
     v.emb_pages = d_emb_pages;
     v.table = d_table;
-    v.rows = cfg.rows;
+    v.rows = tables.empty() ? cfg.rows : tables.back().base + tables.back().rows;
+    v.tables = tables.size() > 1 ? d_tables : nullptr;
+    v.n_tables = static_cast<uint32_t>(tables.size());
     v.counters = d_counters;
     return v;
   }
@@ -273,6 +280,7 @@ int32_t pool_create(void* dev_base, uint64_t bytes, uint64_t page_size, const ra
       void* dp = nullptr;
       e = hipHostGetDevicePointer(&dp, const_cast<void*>(cfg->host_table), 0);
       p->d_table = static_cast<const uint8_t*>(dp);
+      if (e == hipSuccess) p->tables.push_back(racer::TableDesc{0, cfg->rows, p->d_table, cfg->row_bytes, 0});
     }
     if (e != hipSuccess) {
       pool_destroy(p);
@@ -302,6 +310,8 @@ int32_t pool_destroy(racer_pool_t* p) {
         (void)hipEventDestroy(p->ev_join[k]);
       }
     if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
+    (void)hipFree(p->d_tables);
+    (void)hipFree(p->gid_buf);
     (void)hipFree(p->d_tags);
     (void)hipFree(p->d_stamps);
     (void)hipFree(p->d_emb_pages);
@@ -430,6 +440,51 @@ int32_t emb_lookup(racer_pool_t* p, const int64_t* ids, uint64_t n, uint32_t bag
                                         p->batch, stream));
   }
   return RACER_OK;
+}
+
+int32_t pool_add_table(racer_pool_t* p, const void* host_table, uint64_t rows, uint32_t row_bytes, uint32_t* table_out) {
+  if (!p || !p->device || !p->d_table || p->tables.empty() || !host_table) return RACER_EINVAL;
+  if (rows == 0 || row_bytes == 0 || row_bytes % 16 != 0 || row_bytes > p->cfg.row_bytes) return RACER_EINVAL;
+  if (p->tables.size() >= racer::kMaxTables) return RACER_EINVAL;
+  const uint64_t base = p->tables.back().base + p->tables.back().rows;
+  if (base + rows >= 0xFFFFFFFFull) return RACER_EINVAL;  // global ids are the 32-bit cache tags
+  void* dp = nullptr;
+  HIP_TRY(hipHostGetDevicePointer(&dp, const_cast<void*>(host_table), 0));
+  // lookups in flight read the old descriptor array: wait for them, then replace it
+  HIP_TRY(hipStreamSynchronize(p->last_stream));
+  std::vector<racer::TableDesc> next = p->tables;
+  next.push_back(racer::TableDesc{base, rows, static_cast<const uint8_t*>(dp), row_bytes, 0});
+  racer::TableDesc* d_next = nullptr;
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&d_next), sizeof(racer::TableDesc) * next.size()));
+  hipError_t e = hipMemcpy(d_next, next.data(), sizeof(racer::TableDesc) * next.size(), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    (void)hipFree(d_next);
+    return hip_fail(e, "pool_add_table");
+  }
+  if (p->d_tables) (void)hipFree(p->d_tables);
+  p->d_tables = d_next;
+  p->tables.swap(next);
+  if (table_out) *table_out = static_cast<uint32_t>(p->tables.size() - 1);
+  return RACER_OK;
+}
+
+int32_t emb_lookup_tables(racer_pool_t* p, const uint32_t* table_of, const int64_t* ids, uint64_t n, uint32_t bag,
+                          void* out, uint8_t* hit_flags, void* stream_v) {
+  if (!p || !p->device || !p->d_table) return RACER_EINVAL;
+  if (n >= 0xFFFFFFFFull || (n && (!table_of || !ids))) return RACER_EINVAL;
+  if (p->tables.size() < 2) return RACER_EINVAL;  // one table: emb_lookup
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  if (n > p->gid_cap) {
+    HIP_TRY(hipStreamSynchronize(p->last_stream));
+    if (p->gid_buf) HIP_TRY(hipFree(p->gid_buf));
+    p->gid_buf = nullptr;
+    p->gid_cap = 0;
+    const uint64_t cap = std::max<uint64_t>(n, 1024);
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->gid_buf), cap * sizeof(int64_t)));
+    p->gid_cap = cap;
+  }
+  HIP_TRY(racer::launch_emb_global_ids(p->view(), table_of, ids, static_cast<uint32_t>(n), p->gid_buf, stream));
+  return emb_lookup(p, p->gid_buf, n, bag, out, hit_flags, stream_v);
 }
 
 int32_t emb_refill(racer_pool_t* p, const int64_t* ids, uint64_t n, void* stream_v) {

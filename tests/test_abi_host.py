@@ -64,6 +64,8 @@ def test_metadata_only_pool_rejects_device_calls():
     h = host_pool(64, 4, 8, 32, 0.5)
     assert B.load().emb_lookup(h, None, 0, 1, None, None, None) == B.EINVAL
     assert B.load().emb_refill(h, None, 0, None) == B.EINVAL
+    assert B.load().pool_add_table(h, None, 10, 64, None) == B.EINVAL
+    assert B.load().emb_lookup_tables(h, None, None, 0, 1, None, None, None) == B.EINVAL
     assert B.load().emb_cache_dump(h, None, None) == B.EINVAL
     B.pool_destroy(h)
 

@@ -253,3 +253,49 @@ def test_refill_after_growth_restores_hits_without_evicting():
     assert after["evicted"] == before["evicted"] and after["lookups"] == before["lookups"]
     run_batches(pool, orc, table, [synth.zipf_ids(rng, rows, 1.0, 4096) for _ in range(2)], tag="served")
     pool.close()
+
+
+@pytest.mark.parametrize("bf16,bag", [(False, 1), (False, 2), (True, 1), (True, 4)])
+def test_several_tables_of_different_widths_equal_one_padded_table(bf16, bag):
+    # three tables behind one pool, rows of 256, 64 and 128 bytes (bf16: 512, 128, 256): looking rows up by
+    # (table, row) must equal the single-table lookup in the concatenation of the zero-padded tables
+    rng = np.random.default_rng(21 + bag)
+    d = 256 if bf16 else 64  # elements of the pool's rows
+    widths, rows = [d, d // 4, d // 2], [1000, 5000, 300]
+    tables = [synth.make_table(rng, r, w, bf16=bf16) for r, w in zip(rows, widths)]
+    padded = np.zeros((sum(rows), d), dtype=tables[0].dtype)
+    base = np.concatenate([[0], np.cumsum(rows)])
+    for t, tab in enumerate(tables):
+        padded[base[t]: base[t + 1], : widths[t]] = tab
+    esz = 2 if bf16 else 4
+    pinned = [Hn.to_device_table(tab) for tab in tables]
+    pool = Hn.Pool(128, 8 * d * esz, d * esz, B.ELEM_BF16 if bf16 else B.ELEM_F32, 4, 32, pinned[0], 0.5)
+    orc = oracle.Pool(128, 4, 8, 32, 0.5)
+    for t in (1, 2):
+        rc, num = B.pool_add_table(pool.h, pinned[t], rows[t], widths[t] * esz)
+        assert (rc, num) == (B.OK, t), B.last_error()
+    assert B.pool_add_table(pool.h, pinned[1], rows[1], d * esz + 16)[0] == B.EINVAL  # wider than a slot
+    n = 1200
+    for step in range(6):
+        table_of = rng.integers(0, 4, size=n)  # table 3 does not exist
+        ids = np.array([rng.integers(-2, rows[t] + 3) if t < 3 else rng.integers(0, 100) for t in table_of])
+        gids = np.where((table_of < 3) & (ids >= 0) & (ids < np.array(rows + [0])[table_of]),
+                        base[np.minimum(table_of, 2)] + ids, -1).astype(np.int64)
+        out = torch.empty((n // bag, d), dtype=Hn.torch_dtype(pool.elem), device=Hn.DEV)
+        hit = torch.empty(n, dtype=torch.uint8, device=Hn.DEV)
+        rc = B.emb_lookup_tables(pool.h, torch.from_numpy(table_of.astype(np.int32)).to(Hn.DEV),
+                                 torch.from_numpy(ids.astype(np.int64)).to(Hn.DEV), out, bag, hit)
+        assert rc == B.OK, B.last_error()
+        rco, oout, ohit = orc.emb_lookup(gids, padded, bag)
+        assert rco == oracle.OK
+        assert np.array_equal(hit.cpu().numpy(), ohit), step
+        assert np.array_equal(Hn.out_to_numpy(out, pool.elem), oout), step
+        check_state(pool, orc, padded, "tables step %d" % step)
+    # global ids go straight into emb_lookup and emb_refill
+    gids = rng.integers(0, sum(rows), size=500)
+    run_batches(pool, orc, padded, [gids], tag="global ids")
+    refill_both(pool, orc, rng.integers(0, sum(rows), size=700), sum(rows))
+    check_state(pool, orc, padded, "refill over tables")
+    st = pool.stats()
+    assert st["evicted"] > 0 and st["invalid_ids"] > 0  # the cache is smaller than the tables: the pressure is real
+    pool.close()
