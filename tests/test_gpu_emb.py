@@ -299,3 +299,47 @@ def test_several_tables_of_different_widths_equal_one_padded_table(bf16, bag):
     st = pool.stats()
     assert st["evicted"] > 0 and st["invalid_ids"] > 0  # the cache is smaller than the tables: the pressure is real
     pool.close()
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_random_sequences_of_lookups_refills_and_split_moves(seed):
+    # lookups (plain and pooled), refills and boundary moves in random order on a small pool with two tables:
+    # after every operation the device state must be the oracle's
+    rng = np.random.default_rng(500 + seed)
+    d, spp = 32, 8
+    rows = [1500, 700]
+    tables = [rng.standard_normal((rows[0], d)).astype(np.float32), rng.standard_normal((rows[1], d // 2)).astype(np.float32)]
+    padded = np.zeros((sum(rows), d), dtype=np.float32)
+    padded[: rows[0]] = tables[0]
+    padded[rows[0]:, : d // 2] = tables[1]
+    pinned = [Hn.to_device_table(t) for t in tables]
+    n_pages = 96
+    pool = Hn.Pool(n_pages, spp * d * 4, d * 4, B.ELEM_F32, 4, 32, pinned[0], 0.4)
+    orc = oracle.Pool(n_pages, 4, spp, 32, 0.4)
+    assert B.pool_add_table(pool.h, pinned[1], rows[1], d * 2) == (B.OK, 1)
+    total = sum(rows)
+    for step in range(40):
+        op = rng.integers(0, 4)
+        if op == 0:
+            bag = int(rng.choice([1, 2, 3]))
+            ids = rng.integers(-2, total + 2, size=bag * int(rng.integers(0, 200)))
+            run_batches(pool, orc, padded, [ids], bag=bag, tag="step %d lookup" % step)
+        elif op == 1:
+            refill_both(pool, orc, rng.integers(-1, total + 1, size=int(rng.integers(0, 300))), total)
+        elif op == 2:
+            frac = float(rng.choice([0.1, 0.2, 0.35, 0.5, 0.7, 0.9]))
+            rc, ach = B.pool_set_split(pool.h, frac)
+            assert (rc, ach) == orc.set_split(frac), (step, frac)
+        else:
+            n = int(rng.integers(1, 150))
+            table_of = rng.integers(0, 2, size=n)
+            ids = np.array([rng.integers(0, rows[t]) for t in table_of])
+            out = torch.empty((n, d), dtype=torch.float32, device=Hn.DEV)
+            rc = B.emb_lookup_tables(pool.h, torch.from_numpy(table_of.astype(np.int32)).to(Hn.DEV),
+                                     torch.from_numpy(ids.astype(np.int64)).to(Hn.DEV), out, 1, None)
+            assert rc == B.OK, B.last_error()
+            gids = (np.array([0, rows[0]])[table_of] + ids).astype(np.int64)
+            rco, oout, _ = orc.emb_lookup(gids, padded, 1)
+            assert np.array_equal(out.cpu().numpy(), oout), step
+        check_state(pool, orc, padded, "step %d op %d" % (step, op))
+    pool.close()
