@@ -1293,24 +1293,37 @@ __global__ __launch_bounds__(256, NQB == 1 ? 3 : 2) void attention_bf16_mfma(Hst
 __global__ __launch_bounds__(256) void attention_reduce(HstuDims hd, uint32_t q_block, const ReqDev* __restrict__ reqs,
                                                         const AttnGroup* __restrict__ groups,
                                                         const float* __restrict__ partials, uint16_t* __restrict__ o) {
+  // blockIdx.x = (group, head); blockIdx.y = which 16 of the tile's query rows: a thread owns one 16-byte piece of
+  // one row, so that the chunks' loads of a whole tile are in flight at once
   const AttnGroup gr = groups[blockIdx.x / hd.H];
   const uint32_t h = blockIdx.x % hd.H;
   const ReqDev rq = reqs[gr.req];
-  for (uint32_t idx = threadIdx.x; idx < q_block * 16; idx += 256) {
-    const uint32_t row = idx >> 4, c4 = idx & 15;
-    const uint32_t qi = gr.qt * q_block + row;
-    if (qi >= rq.new_len) continue;
-    float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    for (uint32_t k = 0; k < gr.chunks; ++k) {
-      const float4 v = *reinterpret_cast<const float4*>(
-          partials + ((static_cast<uint64_t>(gr.slot0 + k) * hd.H + h) * q_block + row) * 64 + 4 * c4);
-      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-    }
-    uint2 w;
-    w.x = pack_bf16x2(acc.x, acc.y);
-    w.y = pack_bf16x2(acc.z, acc.w);
-    *reinterpret_cast<uint2*>(o + static_cast<uint64_t>(rq.x_off + qi) * hd.d + h * 64 + 4 * c4) = w;
+  const uint32_t idx = blockIdx.y * 256 + threadIdx.x;
+  const uint32_t row = idx >> 4, c4 = idx & 15;
+  const uint32_t qi = gr.qt * q_block + row;
+  if (row >= q_block || qi >= rq.new_len) return;
+  const float* src = partials + ((static_cast<uint64_t>(gr.slot0) * hd.H + h) * q_block + row) * 64 + 4 * c4;
+  const uint64_t step = static_cast<uint64_t>(hd.H) * q_block * 64;  // from one chunk's partial to the next
+  float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  uint32_t k = 0;
+  for (; k + 4 <= gr.chunks; k += 4) {  // four loads in flight; the sum keeps the chunk order
+    const float4 v0 = *reinterpret_cast<const float4*>(src + (k + 0) * step);
+    const float4 v1 = *reinterpret_cast<const float4*>(src + (k + 1) * step);
+    const float4 v2 = *reinterpret_cast<const float4*>(src + (k + 2) * step);
+    const float4 v3 = *reinterpret_cast<const float4*>(src + (k + 3) * step);
+    acc.x += v0.x; acc.y += v0.y; acc.z += v0.z; acc.w += v0.w;
+    acc.x += v1.x; acc.y += v1.y; acc.z += v1.z; acc.w += v1.w;
+    acc.x += v2.x; acc.y += v2.y; acc.z += v2.z; acc.w += v2.w;
+    acc.x += v3.x; acc.y += v3.y; acc.z += v3.z; acc.w += v3.w;
   }
+  for (; k < gr.chunks; ++k) {
+    const float4 v = *reinterpret_cast<const float4*>(src + k * step);
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  }
+  uint2 w;
+  w.x = pack_bf16x2(acc.x, acc.y);
+  w.y = pack_bf16x2(acc.z, acc.w);
+  *reinterpret_cast<uint2*>(o + static_cast<uint64_t>(rq.x_off + qi) * hd.d + h * 64 + 4 * c4) = w;
 }
 
 __global__ void scale_f32(const float* __restrict__ in, float* __restrict__ out, uint64_t n, float s) {
@@ -1474,8 +1487,8 @@ hipError_t launch_attention(const HstuDims& hd, uint32_t layer, const void* q, c
 
 hipError_t launch_attention_reduce(const HstuDims& hd, const StepLists& sl, void* o, hipStream_t stream) {
   if (hd.elem != 1 || sl.n_groups == 0) return hipSuccess;
-  hipLaunchKernelGGL(attention_reduce, dim3(sl.n_groups * hd.H), dim3(256), 0, stream, hd, sl.q_block, sl.reqs,
-                     sl.groups, sl.partials, static_cast<uint16_t*>(o));
+  hipLaunchKernelGGL(attention_reduce, dim3(sl.n_groups * hd.H, (sl.q_block * 16 + 255) / 256), dim3(256), 0, stream, hd,
+                     sl.q_block, sl.reqs, sl.groups, sl.partials, static_cast<uint16_t*>(o));
   return hipGetLastError();
 }
 
