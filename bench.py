@@ -37,6 +37,14 @@ CONFIGS = {
                      bag=8, emb_only=True,
                      desc="EMB-heavy: table 100Mx128 bf16 pinned host, 50 GiB pool @ EMB:KV=0.8 (40 GiB hot cache), "
                           "batch 256 x 1024 tokens x 8 features sum-pooled, Zipf(0.8); lookups only"),
+    # Several tables of different widths behind one hot cache: one lookup per table and token, all tables in one
+    # launch (emb_lookup_tables) against one emb_lookup call per table; the cost per table is what the paper's
+    # Sec. II-B observation (lookup time linear in the number of tables) is about
+    "tables": dict(index=3, L=4, d=128, H=2, bf16=True, rows=2_000_000, pool_bytes=24 << 30, pt=64, alpha=0.8,
+                   tokens=65536, zipf=0.8, n_tables=24, widths=(128, 64, 32), grid=(1, 2, 4, 8, 16, 24),
+                   tables_bench=True,
+                   desc="Tables: up to 24 tables of 2M rows x 128/64/32 bf16 (pinned host) behind one 19 GiB hot cache "
+                        "of 256-byte slots, 65536 tokens x one Zipf(0.8) lookup per table; lookups only"),
     # Long history with KV reuse: the attention kernel alone (one layer) on 512 new tokens per request against a
     # 16k-token cached prefix held in shuffled pages
     "longreuse": dict(index=2, L=8, d=512, H=8, bf16=True, pt=64, batch=32, prefix=16384, new=512, n_time=32,
@@ -698,6 +706,87 @@ def cpu_baseline(c, wl, synth, budget_tokens):
                       "OpenMP over requests (%d threads available)" % (len(take), N, L, dt, threads)}, take, ref
 
 
+def tables_bench(args, c, torch, Hn, B, synth):
+    """emb_lookup_tables over a growing number of tables: one launch for all against one emb_lookup per table."""
+    dev = Hn.DEV
+    d, pt, L, rows, tokens = c["d"], c["pt"], c["L"], c["rows"], c["tokens"]
+    T_max = c["n_tables"]
+    widths = [c["widths"][t % len(c["widths"])] for t in range(T_max)]
+    tables = []
+    for t in range(T_max):
+        tab = torch.empty((rows, widths[t]), dtype=torch.int16, pin_memory=True)
+        synth.fill_table_bf16_torch(tab, synth.SEED_BASE + 100 * c["index"] + t, dev)
+        tables.append(tab)
+    torch.cuda.synchronize()
+    page_size = pt * 2 * L * d * 2
+    n_pages = c["pool_bytes"] // page_size
+    pool = Hn.Pool(n_pages, page_size, d * 2, B.ELEM_BF16, pt, 32, tables[0].view(torch.bfloat16), c["alpha"])
+    for t in range(1, T_max):
+        rc, num = B.pool_add_table(pool.h, tables[t].view(torch.bfloat16), rows, widths[t] * 2)
+        assert (rc, num) == (B.OK, t), (rc, B.last_error())
+    # steady state = a cache that has seen every row (it has more slots than the tables have rows)
+    per = 1 << 21
+    sweep_out = torch.empty((per, d), dtype=torch.bfloat16, device=dev)
+    for lo in range(0, T_max * rows, per):
+        n = min(per, T_max * rows - lo)
+        rc = B.emb_lookup(pool.h, torch.arange(lo, lo + n, dtype=torch.int64, device=dev), sweep_out[:n], 1, None)
+        assert rc == B.OK, (rc, B.last_error())
+    torch.cuda.synchronize()
+    del sweep_out
+    rng = synth.rng_for(c["index"], 17)
+    n_sets = 4
+    out = torch.empty((tokens * T_max, d), dtype=torch.bfloat16, device=dev)
+    per_tables = []
+    for T in c["grid"]:
+        # ids[k]: [token][table] rows inside their tables; the same lookups table after table for the separate calls
+        ids_tok, ids_tab = [], []
+        for k in range(n_sets):
+            cols = np.stack([synth.zipf_ids(rng, rows, c["zipf"], tokens) for _ in range(T)], axis=1)
+            ids_tok.append(torch.from_numpy(cols.reshape(-1).astype(np.int64)).to(dev))
+            glob = cols + np.arange(T, dtype=np.int64)[None, :] * rows
+            ids_tab.append(torch.from_numpy(np.ascontiguousarray(glob.T).astype(np.int64)).to(dev))
+        table_of = torch.arange(T, dtype=torch.int32, device=dev).repeat(tokens)
+        n = tokens * T
+
+        def one_launch(k):
+            rc = B.emb_lookup_tables(pool.h, table_of, ids_tok[k % n_sets], out[:n], 1, None)
+            assert rc == B.OK, (rc, B.last_error())
+
+        def per_table(k):
+            for t in range(T):
+                rc = B.emb_lookup(pool.h, ids_tab[k % n_sets][t], out[t * tokens:(t + 1) * tokens], 1, None)
+                assert rc == B.OK, (rc, B.last_error())
+
+        res = {}
+        for name, fn in (("one_launch", one_launch), ("per_table", per_table)):
+            for k in range(args.warmup):
+                fn(k)
+            torch.cuda.synchronize()
+            st0 = pool.stats()
+            t0 = time.perf_counter()
+            for k in range(args.steps):
+                fn(k)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / args.steps
+            st1 = pool.stats()
+            res[name] = {"ms_per_step": ms, "us_per_table": ms * 1e3 / T,
+                         "hit_rate": (st1["hits"] - st0["hits"]) / max(st1["lookups"] - st0["lookups"], 1)}
+        per_tables.append({"tables": T, "lookups_per_step": n, **res})
+        print("tables %2d: one launch %.3f ms, one call per table %.3f ms" %
+              (T, res["one_launch"]["ms_per_step"], res["per_table"]["ms_per_step"]), file=sys.stderr, flush=True)
+    last = per_tables[-1]
+    ms = last["one_launch"]["ms_per_step"]
+    result = {
+        "metric": "emb_lookup_tables_lookups_per_s", "value": last["lookups_per_step"] / (ms * 1e-3), "unit": "lookups/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": c["desc"], "tokens_per_step": tokens, "tables": last["tables"]},
+        "per_tables": per_tables,
+    }
+    print(json.dumps(result))
+    pool.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -741,6 +830,9 @@ def main():
         return
     if c.get("refill_bench"):
         refill_bench(args, c, torch, Hn, B, synth)
+        return
+    if c.get("tables_bench"):
+        tables_bench(args, c, torch, Hn, B, synth)
         return
     wl = build_workload(c, torch, Hn, B, synth)
     pool = wl["pool"]
