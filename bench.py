@@ -37,6 +37,12 @@ CONFIGS = {
                      bag=8, emb_only=True,
                      desc="EMB-heavy: table 100Mx128 bf16 pinned host, 50 GiB pool @ EMB:KV=0.8 (40 GiB hot cache), "
                           "batch 256 x 1024 tokens x 8 features sum-pooled, Zipf(0.8); lookups only"),
+    # A step that only appends: every request's history is cached, 64 new tokens each.  Every key tile is read once,
+    # by one workgroup, so the attention kernel is measured against HBM here (K and V bytes of the histories)
+    "append": dict(index=4, L=4, d=256, H=4, bf16=True, pt=64, batch=128, mean_len=3072, min_len=512, max_len=12288,
+                   new=64, n_time=32, append_step=True,
+                   desc="Append-only step: 4 layers d=256 H=4 bf16, 128 requests x 64 new tokens behind cached "
+                        "lognormal(mean 3072, 512..12288) histories, KV page 64 tokens, pages shuffled"),
     # Several tables of different widths behind one hot cache: one lookup per table and token, all tables in one
     # launch (emb_lookup_tables) against one emb_lookup call per table; the cost per table is what the paper's
     # Sec. II-B observation (lookup time linear in the number of tables) is about
@@ -706,6 +712,74 @@ def cpu_baseline(c, wl, synth, budget_tokens):
                       "OpenMP over requests (%d threads available)" % (len(take), N, L, dt, threads)}, take, ref
 
 
+def append_step_bench(args, c, torch, Hn, B, synth):
+    """hstu_step on a batch whose histories are all cached: 64 new tokens per request."""
+    dev = Hn.DEV
+    L, d, H, pt, Bq, T = c["L"], c["d"], c["H"], c["pt"], c["batch"], c["new"]
+    rng = synth.rng_for(c["index"] + 1)
+    lens = synth.history_lengths(rng, Bq, c["mean_len"], c["min_len"], c["max_len"])
+    n_pos = c["max_len"]
+    w = synth.make_weights(rng, L, d, H, n_pos, c["n_time"], True)
+    model = Hn.Model(L, d, H, B.ELEM_BF16, pt, n_pos, c["n_time"], float(n_pos), w)
+    page = model.page_size()
+    need = int(sum((int(s_) + pt - 1) // pt for s_ in lens))
+    n_pages = ((need * 4 // 3) // 32 + 1) * 32
+    pool = Hn.Pool(n_pages, page, d * 2, B.ELEM_BF16, pt, 32, None, 0.25, zero_fill=True)
+    first_kv = n_pages // 4
+    perm = first_kv + rng.permutation(n_pages - first_kv)
+    prefix = [int(s_) - T for s_ in lens]
+    reqs, n_pt, n_ts, N = synth.make_requests(prefix, [T] * Bq, pt)
+    pts = torch.from_numpy(perm[:n_pt].astype(np.int32)).to(dev)
+    ts_all = synth.timestamps(rng, c["max_len"])
+    ts = torch.from_numpy(np.concatenate([ts_all[:int(s_)] for s_ in lens])).to(dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4322)
+    for piece in pool.mem.view(torch.bfloat16).split(1 << 28):  # every page: N(0, 0.35^2) keys and values
+        piece.copy_(torch.randn(piece.numel(), generator=gen, device=dev) * 0.35)
+    x = (torch.randn((N, d), generator=gen, device=dev) * 0.5).to(torch.bfloat16)
+    y = torch.empty_like(x)
+    reqs_c = (B.make_reqs(reqs), len(reqs))
+
+    def call():
+        rc = B.hstu_step(pool.h, model.h, reqs_c, pts, x, ts, y)
+        assert rc == B.OK, (rc, B.last_error())
+    for _ in range(args.warmup):
+        call()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        call()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    B.racer_prof_enable(pool.h, 1)
+    B.racer_prof_read(pool.h)
+    for _ in range(args.steps):
+        call()
+    torch.cuda.synchronize()
+    prof = B.racer_prof_read(pool.h)
+    B.racer_prof_enable(pool.h, 0)
+    pairs = float(sum(T * p_ + T * (T + 1) / 2 for p_ in prefix))
+    attn_ms = prof["attention"][0] / max(prof["attention"][1], 1)
+    # K and V of every key of every request, all heads of one layer: 2 * d elements per key
+    kv_bytes = float(sum(int(s_) for s_ in lens)) * 2 * d * 2
+    gbs = kv_bytes / (attn_ms * 1e-3) / 1e9 if attn_ms > 0 else 0.0
+    ms = dt * 1e3 / args.steps
+    print(json.dumps({
+        "metric": "hstu_step_tokens_per_s", "value": N / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": c["desc"], "new_tokens_per_step": int(N), "mean_history": float(np.mean(lens)),
+                   "causal_pairs_per_layer": pairs},
+        "roofline": {"kernel": "attention_bf16_mfma", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "traffic": None, "bytes_per_launch": kv_bytes,
+                     "ms_per_launch": attn_ms, "mfma_tflops": 4.0 * d * pairs / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else 0.0},
+        "kernels": {k: {"ms_per_launch": (v[0] / v[1] if v[1] else 0.0), "launches_per_step": v[1] / args.steps}
+                    for k, v in prof.items() if v[1]},
+    }))
+    model.close()
+    pool.close()
+
+
 def tables_bench(args, c, torch, Hn, B, synth):
     """emb_lookup_tables over a growing number of tables: one launch for all against one emb_lookup per table."""
     dev = Hn.DEV
@@ -833,6 +907,9 @@ def main():
         return
     if c.get("tables_bench"):
         tables_bench(args, c, torch, Hn, B, synth)
+        return
+    if c.get("append_step"):
+        append_step_bench(args, c, torch, Hn, B, synth)
         return
     wl = build_workload(c, torch, Hn, B, synth)
     pool = wl["pool"]
