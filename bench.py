@@ -882,7 +882,7 @@ def main():
         sys.exit(2)
     import torch
     from paper_2605_04450_amd import binding as B
-    from paper_2605_04450_amd import harness as Hn
+    from paper_2605_04450_amd import device as Hn
     from paper_2605_04450_amd import synth
 
     B.load()

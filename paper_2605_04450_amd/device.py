@@ -1,8 +1,6 @@
-"""Glue used by the GPU tests, the smoke check and the benchmark: builds a pool and a model on
-cuda:0 from synthetic inputs and runs the library on them.  No arithmetic of the method lives
-here; everything is computed by the C-ABI library."""
-import math
-
+"""Device-side conveniences over the binding: a pool and a model on cuda:0 whose memory PyTorch
+allocates, and readers/writers of the KV page layout.  No arithmetic of the method lives here;
+everything is computed by the C-ABI library."""
 import numpy as np
 import torch
 
@@ -79,7 +77,7 @@ class Pool:
 
 
 def out_to_numpy(out, elem):
-    """Device output -> numpy in the oracle's convention (fp32, or uint16 bf16 bits)."""
+    """Device output -> numpy: fp32 values, or uint16 holding bf16 bit patterns."""
     if elem == B.ELEM_BF16:
         return out.view(torch.int16).cpu().numpy().view(np.uint16)
     return out.cpu().numpy()
@@ -158,55 +156,3 @@ def read_kv(pool_mem_elems, L, d, H, pt, pages, S, layer):
             K[t0:t1, h * dh:(h + 1) * dh] = pool_mem_elems[ko:ko + (t1 - t0) * dh].view(t1 - t0, dh)
             V[t0:t1, h * dh:(h + 1) * dh] = pool_mem_elems[vo:vo + pt * dh].view(dh, pt)[:, : t1 - t0].t()
     return K, V
-
-
-def rel_error_rows(got, ref):
-    """Row-wise relative error in the max norm: max_i |got_i - ref_i| / max_i |ref_i| per row."""
-    got = np.asarray(got, dtype=np.float64)
-    ref = np.asarray(ref, dtype=np.float64)
-    num = np.abs(got - ref).max(axis=1)
-    den = np.maximum(np.abs(ref).max(axis=1), 1e-30)
-    return num / den
-
-
-def smoke_check():
-    """One tiny serving step (EMB lookup then HSTU step) on cuda:0, checked against the oracle."""
-    import oracle
-    L, d, H, pt, rows = 1, 64, 2, 16, 5000
-    rng = synth.rng_for(0, 99)
-    table = synth.make_table(rng, rows, d, bf16=False)
-    lens = [40, 17]
-    reqs, n_pt, n_ts, N = synth.make_requests([0, 0], lens, pt)
-    n_pos, n_time, n_scale = 64, 16, 64.0
-    w = synth.make_weights(rng, L, d, H, n_pos, n_time, bf16=False)
-    page_size = pt * 2 * L * d * 4
-    n_pages = 64
-    pool = Pool(n_pages, page_size, d * 4, B.ELEM_F32, pt, 32, to_device_table(table), 0.5)
-    model = Model(L, d, H, B.ELEM_F32, pt, n_pos, n_time, n_scale, w)
-    orc = oracle.Pool(n_pages, pt, page_size // (d * 4), 32, 0.5)
-    ids = synth.zipf_ids(rng, rows, 1.0, N)
-    for _ in range(2):
-        x, hit = pool.lookup(torch.from_numpy(ids).to(DEV))
-        rc, ox, ohit = orc.emb_lookup(ids, table)
-        assert np.array_equal(hit.cpu().numpy(), ohit), "hit flags differ from the oracle"
-        assert np.array_equal(x.cpu().numpy(), ox), "gathered rows differ from the oracle"
-    pages = []
-    for key, s in enumerate(lens):
-        rc, pg = B.kv_seq_reserve(pool.h, key, s)
-        assert rc == B.OK
-        assert np.array_equal(pg, orc.kv_reserve(key, s)[1])
-        pages.append(pg)
-    pts = np.concatenate(pages).astype(np.int32)
-    ts = np.concatenate([synth.timestamps(rng, s) for s in lens])
-    out = torch.empty((N, d), dtype=torch.float32, device=DEV)
-    rc = B.hstu_step(pool.h, model.h, reqs, torch.from_numpy(pts).to(DEV), x, torch.from_numpy(ts).to(DEV), out)
-    assert rc == B.OK, (rc, B.last_error())
-    torch.cuda.synchronize()
-    cfg = oracle.make_cfg(L, d, H, pt, n_pos, n_time, n_scale, 1e-6, False)
-    kv = np.zeros(n_pages * oracle.kv_elems_per_page(cfg), dtype=np.float32)
-    rc, ref = oracle.hstu_step(cfg, w, reqs, pts, kv, ox, ts)
-    err = rel_error_rows(out.cpu().numpy(), ref).max()
-    assert err < 1e-4, "hstu_step differs from the oracle: %g" % err
-    assert pool.stats()["bad_pages"] == 0
-    model.close()
-    pool.close()

@@ -6,7 +6,7 @@ import torch
 
 import oracle
 from paper_2605_04450_amd import binding as B
-from paper_2605_04450_amd import harness as Hn
+from paper_2605_04450_amd import device as Hn
 from paper_2605_04450_amd import synth
 
 pytestmark = pytest.mark.gpu

@@ -1,21 +1,19 @@
 """GPU parity of hstu_step / hstu_attn_paged against the fp64 oracle.
 
-Tolerance (row-wise relative error in the max norm, max_i|gpu_i - ref_i| / max_i|ref_i| per
-output row): 1e-4 for fp32 models, 2e-2 for bf16 models whose intermediates are rounded to
-bf16 while the oracle rounds only the stored K,V."""
+Tolerances: tests/parity.py (two relative measures per output row, 1e-4 for fp32 models; for bf16
+models, whose intermediates are rounded to bf16 while the oracle rounds only the stored K,V, 2e-2 in
+the row's max norm)."""
 import numpy as np
 import pytest
 import torch
 
 import oracle
 from paper_2605_04450_amd import binding as B
-from paper_2605_04450_amd import harness as Hn
+from paper_2605_04450_amd import device as Hn
 from paper_2605_04450_amd import synth
+from tests import parity
 
 pytestmark = pytest.mark.gpu
-
-TOL = {False: 1e-4, True: 2e-2}
-
 
 class Case:
     """One model + pool on the device and the matching oracle state."""
@@ -79,9 +77,7 @@ class Case:
 
 
 def assert_close(got, ref, bf16, what=""):
-    err = Hn.rel_error_rows(got, ref)
-    assert np.isfinite(got).all(), what
-    assert err.max() <= TOL[bf16], (what, float(err.max()), int(err.argmax()))
+    parity.assert_close(got, ref, bf16, what)
 
 
 def test_tiny_config_fp32_full_output_and_stored_kv():

@@ -15,7 +15,7 @@ import torch.nn.functional as F
 
 import oracle
 from paper_2605_04450_amd import synth
-from test_oracle_pool import golden
+from tests.test_oracle_pool import golden
 
 
 def build_case(seed, L, d, H, pt, prefix, new, n_pos=None, n_time=8, bf16=False, shuffle_pages=True,
