@@ -27,6 +27,14 @@
 
 #include "racer_oracle.h"
 
+static int omp_in_parallel_(void) {
+#ifdef _OPENMP
+  return omp_in_parallel();
+#else
+  return 1;
+#endif
+}
+
 uint16_t orc_f32_to_bf16_bits(float x) {
   uint32_t u;
   memcpy(&u, &x, 4);
@@ -84,6 +92,9 @@ void orc_attn_paged(const orc_hstu_cfg* cfg, uint32_t layer, const float* pos, c
                     uint32_t P, uint32_t T, const int32_t* pages, const int64_t* ts,
                     const float* kv_mem, const double* q, double* o) {
   const uint32_t d = cfg->d, H = cfg->H, dh = d / H, pt = cfg->page_tokens;
+  /* (head, query) pairs are independent of one another; a caller that is not itself inside a
+   * parallel region (one request at a time) spreads them over the threads */
+#pragma omp parallel for collapse(2) schedule(dynamic, 8) if (!omp_in_parallel_())
   for (uint32_t h = 0; h < H; ++h) {
     for (uint32_t i = 0; i < T; ++i) {
       const uint32_t p = P + i;
@@ -114,12 +125,9 @@ static void step_one_request(const orc_hstu_cfg* cfg, const orc_hstu_weights* w,
   const int32_t* pages = page_tables + rq->page_table_off;
   const int64_t* ts = ts_all + rq->ts_off;
   double* X = (double*)malloc(sizeof(double) * T * d);
-  double* Xn = (double*)malloc(sizeof(double) * d);
-  double* Z = (double*)malloc(sizeof(double) * 4 * d);
   double* U = (double*)malloc(sizeof(double) * T * d);
   double* Q = (double*)malloc(sizeof(double) * T * d);
   double* O = (double*)malloc(sizeof(double) * T * d);
-  double* G = (double*)malloc(sizeof(double) * d);
   for (uint64_t e = 0; e < (uint64_t)T * d; ++e) X[e] = (double)x_in[rq->x_off * d + e];
 
   for (uint32_t l = 0; l < L; ++l) {
@@ -127,8 +135,11 @@ static void step_one_request(const orc_hstu_cfg* cfg, const orc_hstu_weights* w,
     const float* b1 = w->b1 + (uint64_t)l * 4 * d;
     const float* w2 = w->w2 + (uint64_t)l * d * d;
     const float* b2 = w->b2 + (uint64_t)l * d;
-    /* pointwise projection, then K,V of the new tokens go into the pages */
+    /* pointwise projection, then K,V of the new tokens go into the pages (tokens are independent
+     * here: each has scratch of its own) */
+#pragma omp parallel for schedule(static) if (!omp_in_parallel_())
     for (uint32_t i = 0; i < T; ++i) {
+      double Xn[d], Z[4 * d];
       orc_layernorm(X + (uint64_t)i * d, w->ln1_g + (uint64_t)l * d, w->ln1_b + (uint64_t)l * d, d,
                     cfg->eps, Xn);
       for (uint32_t c = 0; c < 4 * d; ++c) {
@@ -153,7 +164,9 @@ static void step_one_request(const orc_hstu_cfg* cfg, const orc_hstu_weights* w,
     orc_attn_paged(cfg, l, w->pos + (uint64_t)l * H * cfg->n_pos,
                    w->time + (uint64_t)l * H * cfg->n_time, P, T, pages, ts, kv_mem, Q, O);
     /* gated transformation with residual */
+#pragma omp parallel for schedule(static) if (!omp_in_parallel_())
     for (uint32_t i = 0; i < T; ++i) {
+      double G[d], Xn[d];
       orc_layernorm(O + (uint64_t)i * d, w->ln2_g + (uint64_t)l * d, w->ln2_b + (uint64_t)l * d, d,
                     cfg->eps, G);
       for (uint32_t c = 0; c < d; ++c) G[c] *= U[(uint64_t)i * d + c];
@@ -166,12 +179,9 @@ static void step_one_request(const orc_hstu_cfg* cfg, const orc_hstu_weights* w,
     }
   }
   memcpy(out + rq->x_off * d, X, sizeof(double) * T * d);
-  free(G);
   free(O);
   free(Q);
   free(U);
-  free(Z);
-  free(Xn);
   free(X);
 }
 
@@ -193,7 +203,8 @@ int orc_hstu_step(const orc_hstu_cfg* cfg, const orc_hstu_weights* w, const orc_
 #else
   (void)threads;
 #endif
-#pragma omp parallel for schedule(dynamic, 1)
+  /* (a single request is served by the threads inside it instead) */
+#pragma omp parallel for schedule(dynamic, 1) if (B > 1)
   for (int r = 0; r < (int)B; ++r)
     step_one_request(cfg, w, &reqs[r], page_tables, kv_mem, x_in, ts, out);
   return ORC_OK;

@@ -305,14 +305,17 @@ def test_page_table_permutation_and_page_size_do_not_change_outputs():
 
 def test_requests_are_independent_and_threads_do_not_change_results():
     prefix, new = [0, 0, 0, 0], [7, 12, 3, 9]
-    cfg, w, reqs, pts, ts, x, kv = build_case(12, 1, 16, 2, 4, prefix, new, n_pos=12, n_scale=12.0)
-    rc, one = oracle.hstu_step(cfg, w, reqs, pts, kv.copy(), x, ts, threads=1)
-    rc, many = oracle.hstu_step(cfg, w, reqs, pts, kv.copy(), x, ts, threads=4)
-    assert np.array_equal(one, many)
-    # a request served alone gives the same rows
-    (P, T, pto, tso, xo) = reqs[2]
-    rc, alone = oracle.hstu_step(cfg, w, [(P, T, pto, tso, 0)], pts, kv.copy(), x[xo:xo + T], ts)
-    assert np.array_equal(alone, one[xo:xo + T])
+    cfg, w, reqs, pts, ts, x, kv = build_case(12, 2, 16, 2, 4, prefix, new, n_pos=12, n_scale=12.0)
+    kv1, kv4, kva = kv.copy(), kv.copy(), kv.copy()
+    rc, one = oracle.hstu_step(cfg, w, reqs, pts, kv1, x, ts, threads=1)
+    rc, many = oracle.hstu_step(cfg, w, reqs, pts, kv4, x, ts, threads=4)
+    assert np.array_equal(one, many) and np.array_equal(kv1, kv4)
+    # requests served alone, one call each (the threads then work inside the request: over its tokens in
+    # the projections, over (head, query) pairs in the attention), give the same rows and the same stored K,V
+    for (P, T, pto, tso, xo) in reqs:
+        rc, alone = oracle.hstu_step(cfg, w, [(P, T, pto, tso, 0)], pts, kva, x[xo:xo + T], ts, threads=4)
+        assert np.array_equal(alone, one[xo:xo + T])
+    assert np.array_equal(kva, kv1)
 
 
 def test_page_table_out_of_range_is_rejected():
