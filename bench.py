@@ -990,6 +990,19 @@ def main():
         budget = args.cpu_tokens or (1024 if args.config == "tiny" else 56000)
         cb, take, ref = cpu_baseline(c, wl, synth, budget)
         result["cpu_baseline"] = cb
+        # the oracle's outputs for its sample are compared with the GPU's for the same requests (same ids:
+        # the first id set), with the measures of the parity tests
+        from tests import parity
+        one_step(wl, 0, B)
+        torch.cuda.synchronize()
+        got = wl["out"].float().cpu().numpy()
+        rows = np.concatenate([np.arange(wl["reqs"][r][4], wl["reqs"][r][4] + int(wl["lens"][r])) for r in take])
+        result["parity_max_rel_err"] = float(parity.rel_error_rows(got[rows], ref).max())
+        result["parity"] = {"measure": "max over rows of max_i|gpu-ref| / max_i|ref|, fp64 oracle",
+                            "rows": int(len(rows)), "requests": len(take),
+                            "row_norm": result["parity_max_rel_err"],
+                            "elementwise_floor_1e-2": float(parity.rel_error_elem(got[rows], ref).max()),
+                            "tolerance_row_norm": parity.TOL_ROW[bool(c["bf16"])]}
     print(json.dumps(result))
     wl["model"].close()
     pool.close()

@@ -31,12 +31,15 @@ int32_t hip_fail(hipError_t e, const char* what) {
 
 bool is_pow2(uint64_t x) { return x && !(x & (x - 1)); }
 
+// Device memory for metadata and workspaces.  With `zero` the memory is cleared by a fill kernel on `stream`,
+// the stream whose later kernels use it (a clear on the null stream is not ordered with a non-blocking stream).
 template <typename T>
-int32_t dev_alloc(T** p, uint64_t count, bool zero) {
+int32_t dev_alloc(T** p, uint64_t count, bool zero, hipStream_t stream) {
   *p = nullptr;
   if (count == 0) count = 1;
-  HIP_TRY(hipMalloc(reinterpret_cast<void**>(p), count * sizeof(T)));
-  if (zero) HIP_TRY(hipMemset(*p, 0, count * sizeof(T)));
+  const uint64_t bytes = (count * sizeof(T) + 3) & ~3ull;  // cleared in 32-bit words
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(p), bytes));
+  if (zero) HIP_TRY(racer::launch_fill_u32(reinterpret_cast<uint32_t*>(*p), bytes / 4, 0u, stream));
   return RACER_OK;
 }
 
@@ -203,7 +206,7 @@ void free_miss_ws(racer_pool* p) {
   p->ws_cap = 0;
 }
 
-int32_t ensure_miss_ws(racer_pool* p, uint64_t n) {
+int32_t ensure_miss_ws(racer_pool* p, uint64_t n, hipStream_t stream) {
   if (n <= p->ws_cap) return RACER_OK;
   if (p->ws_cap) {
     HIP_TRY(hipStreamSynchronize(p->last_stream));
@@ -214,20 +217,20 @@ int32_t ensure_miss_ws(racer_pool* p, uint64_t n) {
   while (hsize < 2 * cap) hsize <<= 1;
   racer::MissWs& w = p->ws;
   int32_t rc;
-  if ((rc = dev_alloc(&p->ws_ctr, 8, true))) return rc;
-  if ((rc = dev_alloc(&w.miss_list, cap, false))) return rc;
-  if ((rc = dev_alloc(&w.def_list, cap, false))) return rc;
-  if ((rc = dev_alloc(&w.loc, cap, false))) return rc;
-  if ((rc = dev_alloc(&w.hkeys, hsize, true))) return rc;
-  if ((rc = dev_alloc(&w.hvals, hsize, true))) return rc;
-  if ((rc = dev_alloc(&w.hslot_u, hsize, false))) return rc;
-  if ((rc = dev_alloc(&w.heads, hsize, true))) return rc;
-  if ((rc = dev_alloc(&w.u_i, cap, false))) return rc;
-  if ((rc = dev_alloc(&w.u_id, cap, false))) return rc;
-  if ((rc = dev_alloc(&w.u_set, cap, false))) return rc;
-  if ((rc = dev_alloc(&w.u_next, cap, false))) return rc;
-  if ((rc = dev_alloc(&w.u_way, cap, false))) return rc;
-  if ((rc = dev_alloc(&w.staging, cap * p->cfg.row_bytes, false))) return rc;
+  if ((rc = dev_alloc(&p->ws_ctr, 8, true, stream))) return rc;
+  if ((rc = dev_alloc(&w.miss_list, cap, false, stream))) return rc;
+  if ((rc = dev_alloc(&w.def_list, cap, false, stream))) return rc;
+  if ((rc = dev_alloc(&w.loc, cap, false, stream))) return rc;
+  if ((rc = dev_alloc(&w.hkeys, hsize, true, stream))) return rc;
+  if ((rc = dev_alloc(&w.hvals, hsize, true, stream))) return rc;
+  if ((rc = dev_alloc(&w.hslot_u, hsize, false, stream))) return rc;
+  if ((rc = dev_alloc(&w.heads, hsize, true, stream))) return rc;
+  if ((rc = dev_alloc(&w.u_i, cap, false, stream))) return rc;
+  if ((rc = dev_alloc(&w.u_id, cap, false, stream))) return rc;
+  if ((rc = dev_alloc(&w.u_set, cap, false, stream))) return rc;
+  if ((rc = dev_alloc(&w.u_next, cap, false, stream))) return rc;
+  if ((rc = dev_alloc(&w.u_way, cap, false, stream))) return rc;
+  if ((rc = dev_alloc(&w.staging, cap * p->cfg.row_bytes, false, stream))) return rc;
   w.hmask = static_cast<uint32_t>(hsize - 1);
   w.headmask = static_cast<uint32_t>(hsize - 1);
   p->ws_cap = cap;
@@ -266,9 +269,9 @@ int32_t pool_create(void* dev_base, uint64_t bytes, uint64_t page_size, const ra
   if (p->device) {
     int32_t rc = RACER_OK;
     const uint64_t n_tags = sets * cfg->w_max;
-    if ((rc = dev_alloc(&p->d_tags, n_tags, false)) || (rc = dev_alloc(&p->d_stamps, n_tags, true)) ||
-        (rc = dev_alloc(&p->d_emb_pages, n_pages, true)) ||
-        (rc = dev_alloc(&p->d_counters, racer::kCtrCount * racer::kCtrShards, true))) {
+    if ((rc = dev_alloc(&p->d_tags, n_tags, false, nullptr)) || (rc = dev_alloc(&p->d_stamps, n_tags, true, nullptr)) ||
+        (rc = dev_alloc(&p->d_emb_pages, n_pages, true, nullptr)) ||
+        (rc = dev_alloc(&p->d_counters, racer::kCtrCount * racer::kCtrShards, true, nullptr))) {
       pool_destroy(p);
       return rc;
     }
@@ -422,7 +425,7 @@ int32_t emb_lookup(racer_pool_t* p, const int64_t* ids, uint64_t n, uint32_t bag
   hipStream_t stream = static_cast<hipStream_t>(stream_v);
   p->batch += 1;  // one call = one LRU batch, empty or not
   if (n == 0) return RACER_OK;
-  int32_t rc = ensure_miss_ws(p, n);
+  int32_t rc = ensure_miss_ws(p, n, stream);
   if (rc) return rc;
   racer::MissWs ws = p->ws;
   ws.ctr = p->ws_ctr + 4 * (p->launches & 1);
@@ -493,7 +496,7 @@ int32_t emb_refill(racer_pool_t* p, const int64_t* ids, uint64_t n, void* stream
   hipStream_t stream = static_cast<hipStream_t>(stream_v);
   p->batch += 1;  // a batch of its own in LRU time (and a fresh key for the dedupe table)
   if (n == 0) return RACER_OK;
-  int32_t rc = ensure_miss_ws(p, n);
+  int32_t rc = ensure_miss_ws(p, n, stream);
   if (rc) return rc;
   racer::MissWs ws = p->ws;
   ws.ctr = p->ws_ctr + 4 * (p->launches & 1);

@@ -182,7 +182,79 @@ def test_long_history_config_attention_on_cached_prefix():
     pool.close()
 
 
-def test_mid_config_step_full_batch_short_requests_against_oracle():
+def test_long_history_config_whole_step_against_oracle():
+    # Long history through hstu_step: 8 layers, d = 512, 8 heads, bf16; 32 requests x (16 384 cached + 512 new)
+    # tokens, the cached K,V of every layer synthetic and written straight into shuffled pages.  The oracle
+    # serves two of the requests (all 512 new tokens, all layers, all heads), one call each.
+    L, d, H, pt, P, T, Bq = 8, 512, 8, 64, 16384, 512, 32
+    n_pos, n_time, n_scale = 16896, 32, 16896.0
+    rng = synth.rng_for(2, 1)
+    w = synth.make_weights(rng, L, d, H, n_pos, n_time, True)
+    model = Hn.Model(L, d, H, B.ELEM_BF16, pt, n_pos, n_time, n_scale, w)
+    page = model.page_size()
+    pages_per_req = (P + T + pt - 1) // pt
+    n_pages = ((Bq * pages_per_req * 4 // 3) // 32 + 1) * 32
+    pool = Hn.Pool(n_pages, page, d * 2, B.ELEM_BF16, pt, 32, None, 0.25)
+    first_kv = n_pages // 4
+    perm = first_kv + rng.permutation(n_pages - first_kv)
+    reqs, n_pt, n_ts, N = synth.make_requests([P] * Bq, [T] * Bq, pt)
+    pts = perm[:n_pt].astype(np.int32)
+    ts = np.concatenate([synth.timestamps(rng, P + T) for _ in range(Bq)])
+    # the pool as [page][layer][K|V][head][pt * 64] (a K block is [token][d_h], a V block [d_h][token])
+    mem = pool.mem.view(torch.bfloat16).view(n_pages, L, 2, H, pt * 64)
+    gen = torch.Generator(device=Hn.DEV)
+    gen.manual_seed(4321)
+    sample = (3, 28)
+    kv_host = {}
+    for r in range(Bq):
+        pg = torch.from_numpy(pts[reqs[r][2]: reqs[r][2] + pages_per_req].astype(np.int64)).to(Hn.DEV)
+        for l in range(L):
+            k = (torch.randn((P + T, d), generator=gen, device=Hn.DEV) * (64 ** -0.25)).to(torch.bfloat16)
+            v = torch.randn((P + T, d), generator=gen, device=Hn.DEV).to(torch.bfloat16)
+            mem[pg, l, 0] = k.view(pages_per_req, pt, H, 64).permute(0, 2, 1, 3).reshape(pages_per_req, H, pt * 64)
+            mem[pg, l, 1] = v.view(pages_per_req, pt, H, 64).permute(0, 2, 3, 1).reshape(pages_per_req, H, pt * 64)
+            if r in sample:
+                kv_host[(r, l)] = (k.float().cpu().numpy(), v.float().cpu().numpy())
+    x = synth.as_bf16_values(rng.standard_normal((N, d)).astype(np.float32))
+    xd = torch.from_numpy(x).to(Hn.DEV).to(torch.bfloat16)
+    out = torch.empty_like(xd)
+    rc = B.hstu_step(pool.h, model.h, reqs, torch.from_numpy(pts).to(Hn.DEV), xd, torch.from_numpy(ts).to(Hn.DEV), out)
+    assert rc == B.OK, B.last_error()
+    torch.cuda.synchronize()
+    assert pool.stats()["bad_pages"] == 0
+    got = out.float().cpu().numpy()
+    assert np.isfinite(got).all()
+    cfg = oracle.make_cfg(L, d, H, pt, n_pos, n_time, n_scale, 1e-6, True)
+    per_page = oracle.kv_elems_per_page(cfg)
+    for r in sample:
+        (P_, T_, pto, tso, xo) = reqs[r]
+        # the oracle's own page layout ([layer][K|V][head][token][d_h]) under an identity page table
+        okv = np.zeros((pages_per_req, L, 2, H, pt, 64), dtype=np.float32)
+        for l in range(L):
+            kk, vv = kv_host[(r, l)]
+            okv[:, l, 0] = kk.reshape(pages_per_req, pt, H, 64).transpose(0, 2, 1, 3)
+            okv[:, l, 1] = vv.reshape(pages_per_req, pt, H, 64).transpose(0, 2, 1, 3)
+        okv = okv.reshape(-1)
+        for (j, l, kvi, h) in ((0, 0, 0, 0), (16383, 7, 1, 5), (777, 3, 0, 7)):  # the layout above is the oracle's
+            off = oracle.kv_offset(cfg, j // pt, l, kvi, h, j % pt)
+            assert np.array_equal(okv[off:off + 64], kv_host[(r, l)][kvi][j, h * 64:(h + 1) * 64])
+        rc, ref = oracle.hstu_step(cfg, w, [(P, T, 0, 0, 0)], np.arange(pages_per_req, dtype=np.int32), okv,
+                                   x[xo:xo + T], ts[tso:tso + P + T])
+        assert rc == oracle.OK
+        parity.assert_close(got[xo:xo + T], ref, True, "long history, whole step, request %d" % r)
+        # K,V of the new tokens as the last layer stored them
+        pg = pts[pto:pto + pages_per_req]
+        Kg, Vg = Hn.read_kv(pool.mem.view(torch.bfloat16), L, d, H, pt, pg, P + T, L - 1)
+        o6 = okv.reshape(pages_per_req, L, 2, H, pt, 64)
+        Ko = o6[:, L - 1, 0].transpose(0, 2, 1, 3).reshape(-1, d)[P:P + T]
+        Vo = o6[:, L - 1, 1].transpose(0, 2, 1, 3).reshape(-1, d)[P:P + T]
+        parity.assert_close(Kg[P:].float().cpu().numpy(), Ko, True, "long history, stored K of the new tokens")
+        parity.assert_close(Vg[P:].float().cpu().numpy(), Vo, True, "long history, stored V of the new tokens")
+    model.close()
+    pool.close()
+
+
+def test_mid_config_step_full_batch_short_and_longest_requests_against_oracle():
     # Mid model (4 layers, d = 256, 4 heads, bf16, 64-token pages) on the benchmark's batch of 64 lognormal
     # histories; the oracle recomputes the shortest requests in full (requests are independent)
     L, d, H, pt = 4, 256, 4, 64
@@ -220,11 +292,18 @@ def test_mid_config_step_full_batch_short_requests_against_oracle():
     rc, ref = oracle.hstu_step(cfg, w, sreqs, np.arange(s_pt, dtype=np.int32), kv, sx, sts)
     sg = np.concatenate([got[reqs[r][4]: reqs[r][4] + lens[r]] for r in take])
     parity.assert_close(sg, ref, True, "Mid, six shortest requests")
-    # the longest request, served in two steps (prefix cached, then the tail), agrees with the one-step result
+    # the longest request of the batch (several thousand tokens: its query tiles are cut into key ranges, it
+    # is spread over the dies' work lists and sits in one of the three pipelines): the oracle serves it alone
     r = int(np.argmax(lens))
     S = int(lens[r])
-    cut = (S * 3 // 4) // 8 * 8 + 3
+    assert S >= 4096
     (P_, T_, pto, tso, xo) = reqs[r]
+    lreqs, l_pt, l_ts, lN = synth.make_requests([0], [S], pt)
+    kv = np.zeros(l_pt * oracle.kv_elems_per_page(cfg), dtype=np.float32)
+    rc, ref = oracle.hstu_step(cfg, w, lreqs, np.arange(l_pt, dtype=np.int32), kv, x[xo:xo + S], ts[tso:tso + S])
+    parity.assert_close(got[xo:xo + S], ref, True, "Mid, longest request (%d tokens)" % S)
+    # the same request served in two steps (prefix cached, then the tail) agrees with the one-step result
+    cut = (S * 3 // 4) // 8 * 8 + 3
     ptd, tsd = torch.from_numpy(pts).to(Hn.DEV), torch.from_numpy(ts).to(Hn.DEV)
     o1 = torch.empty((cut, d), dtype=torch.bfloat16, device=Hn.DEV)
     o2 = torch.empty((S - cut, d), dtype=torch.bfloat16, device=Hn.DEV)
@@ -239,8 +318,12 @@ def test_mid_config_step_full_batch_short_requests_against_oracle():
 
 
 def test_split_sweep_config_pages_and_cache_follow_the_oracle():
-    # Split sweep: 128 GiB pool of 256 KiB pages, EMB fraction 0.2 .. 0.8 in steps of 0.05 and back,
-    # Zipf(0.9) lookups between the moves, resident KV sequences keep their pages and bytes
+    # Split sweep: 128 GiB pool of 256 KiB pages, table 100M x 256 bf16.  The hot cache is first filled at 0.8
+    # with one refill sweep over the whole table (a dozen rows per set), then the EMB fraction walks the whole
+    # grid 0.80, 0.75, .. 0.20 (every move evicts the least recently used entries of every set and compacts the
+    # survivors out of the released pages: millions of rows move) and back up to 0.80, with a Zipf(0.9) lookup
+    # batch after every move.  Hit flags, counters, tags, stamps and sampled resident rows follow the oracle;
+    # resident KV sequences keep their pages and bytes.
     # (if the host cannot pin the 51.2 GB table, rows and pool are halved together, keeping the cache/table
     # ratio and the fraction grid; the scale actually used is printed)
     rows, d, pt, L = 100_000_000, 256, 64, 4
@@ -256,8 +339,8 @@ def test_split_sweep_config_pages_and_cache_follow_the_oracle():
     print("split sweep at %d table rows, %d GiB pool" % (rows, pool_bytes >> 30))
     page = pt * 2 * L * d * 2
     n_pages = pool_bytes // page
-    pool = Hn.Pool(n_pages, page, d * 2, B.ELEM_BF16, pt, 32, table.view(torch.bfloat16), 0.2)
-    orc = oracle.Pool(n_pages, pt, page // (d * 2), 32, 0.2)
+    pool = Hn.Pool(n_pages, page, d * 2, B.ELEM_BF16, pt, 32, table.view(torch.bfloat16), 0.8)
+    orc = oracle.Pool(n_pages, pt, page // (d * 2), 32, 0.8)
     rng = synth.rng_for(4, 7)
     lens = synth.history_lengths(rng, 128, 4096, 512, 12288)
     kv_pages = {}
@@ -273,21 +356,36 @@ def test_split_sweep_config_pages_and_cache_follow_the_oracle():
             mem_pages[int(pg[k])] = (key * 7 + k) % 251
             marks[(key, k)] = (key * 7 + k) % 251
     torch.cuda.synchronize()
+    # fill: every row of the table once, in pieces (each piece is one refill batch, so stamps differ by piece)
+    piece = 1 << 22
+    for lo in range(0, rows, piece):
+        n = min(piece, rows - lo)
+        assert B.emb_refill(pool.h, torch.arange(lo, lo + n, dtype=torch.int64, device=Hn.DEV)) == B.OK, B.last_error()
+        rc, ins = orc.emb_refill(np.arange(lo, lo + n, dtype=np.int64), rows)
+        assert rc == oracle.OK
+    filled = pool.stats()["inserted"]
+    assert filled == orc.stats()["inserted"] and filled > 0.99 * rows
     n = 128 * 1024
-    fracs = [0.25, 0.4, 0.8, 0.75, 0.5, 0.3, 0.2]
-    for frac in fracs:
+    grid = [round(0.80 - 0.05 * k, 2) for k in range(13)]  # 0.80 .. 0.20
+    walk = grid[1:] + grid[-2::-1]                        # down to 0.20, back up to 0.80
+    for step, frac in enumerate(walk):
         rc, ach = B.pool_set_split(pool.h, frac)
         assert (rc, ach) == orc.set_split(frac), frac
-        for b in range(2):
-            ids = synth.zipf_ids(rng, rows, 0.9, n)
-            out, hit = pool.lookup(torch.from_numpy(ids).to(Hn.DEV))
-            rc, _, ohit = orc.emb_lookup(ids, _rows_only(rows, d), want_out=False)
-            assert np.array_equal(hit.cpu().numpy(), ohit), (frac, b)
-            pick = rng.integers(0, n, size=2000)
-            got = out[torch.from_numpy(pick).to(Hn.DEV)].view(torch.int16).cpu().numpy().view(np.uint16)
-            assert np.array_equal(got, table_rows_np(table, ids[pick])), (frac, b)
+        ids = synth.zipf_ids(rng, rows, 0.9, n)
+        out, hit = pool.lookup(torch.from_numpy(ids).to(Hn.DEV))
+        rc, _, ohit = orc.emb_lookup(ids, _rows_only(rows, d), want_out=False)
+        assert np.array_equal(hit.cpu().numpy(), ohit), (frac, step)
+        pick = rng.integers(0, n, size=2000)
+        got = out[torch.from_numpy(pick).to(Hn.DEV)].view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(got, table_rows_np(table, ids[pick])), (frac, step)
+        st, so = pool.stats(), orc.stats()
+        for k in ("hits", "misses", "inserted", "evicted", "bypassed", "shrink_evicted", "shrink_moved", "pages_emb"):
+            assert st[k] == so[k], (frac, k, st[k], so[k])
         for (key, k), val in marks.items():  # KV pages never move and keep their bytes
             assert np.array_equal(B.kv_seq_lookup(pool.h, key)[2], kv_pages[key])
             assert bool((mem_pages[int(kv_pages[key][k])] == val).all()), (frac, key, k)
-    check_cache_state(pool, orc, table)  # includes the shrink counters
+        if frac == grid[-1]:  # at the bottom of the walk: the whole cache state, rows included
+            assert st["shrink_moved"] > rows // 100 and st["shrink_evicted"] > rows // 10, st
+            check_cache_state(pool, orc, table)
+    check_cache_state(pool, orc, table)
     pool.close()

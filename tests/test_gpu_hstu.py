@@ -111,8 +111,8 @@ def test_bf16_prefill_ragged_lengths(L, d, H, pt, lens):
     pages = pts[pto:pto + (T + pt - 1) // pt]
     Kg, Vg = Hn.read_kv(c.mem, c.L, c.d, c.H, c.pt, pages, T, L - 1)
     Ko, Vo = c.oracle_kv_rows(pages, T, L - 1)
-    assert np.abs(Kg.float().cpu().numpy() - Ko).max() <= 3e-2 * max(1.0, np.abs(Ko).max())
-    assert np.abs(Vg.float().cpu().numpy() - Vo).max() <= 3e-2 * max(1.0, np.abs(Vo).max())
+    assert_close(Kg.float().cpu().numpy(), Ko, True, "bf16 prefill stored K")
+    assert_close(Vg.float().cpu().numpy(), Vo, True, "bf16 prefill stored V")
     assert c.pool.stats()["bad_pages"] == 0
     c.close()
 
@@ -135,13 +135,18 @@ def test_bf16_long_sequences_use_split_key_ranges():
     c.close()
 
 
-@pytest.mark.parametrize("bf16", [False, True])
-def test_prefix_reuse_two_steps(bf16):
+@pytest.mark.parametrize("bf16,L,d,H,pt,first,more", [
+    (False, 2, 64, 2, 16, [200, 77, 130], [60, 140, 1]),
+    (True, 2, 128, 2, 16, [200, 77, 130], [60, 140, 1]),
+    # the width of the long-history configuration (d = 512, 8 heads): separate LayerNorm + GEMM kernels,
+    # ragged lengths, row tiles with a tail, a request that gets nothing in the second step
+    (True, 2, 512, 8, 64, [300, 129, 64, 1, 515], [70, 1, 130, 64, 0]),
+])
+def test_prefix_reuse_two_steps(bf16, L, d, H, pt, first, more):
     # step 1 prefills, step 2 scores new tokens against the cached prefix (KV reuse)
-    L, d, H, pt = (2, 128, 2, 16) if bf16 else (2, 64, 2, 16)
-    c = Case(3, L, d, H, pt, bf16, 512, 16, 512.0, 128)
-    first, more = [200, 77, 130], [60, 140, 1]
-    reqs1, pts, ts, x_all = c.inputs([0, 0, 0], [a + b for a, b in zip(first, more)])
+    c = Case(3, L, d, H, pt, bf16, 1024, 16, 1024.0, 128)
+    nreq = len(first)
+    reqs1, pts, ts, x_all = c.inputs([0] * nreq, [a + b for a, b in zip(first, more)])
     # carve the two steps out of the same page tables / timestamps
     def step_inputs(prefix, new, take_from):
         reqs, rows = [], []
@@ -151,12 +156,21 @@ def test_prefix_reuse_two_steps(bf16):
             rows.append(x_all[xoff + take_from[r]: xoff + take_from[r] + new[r]])
             xo += new[r]
         return reqs, np.concatenate(rows)
-    ra, xa = step_inputs([0, 0, 0], first, [0, 0, 0])
+    ra, xa = step_inputs([0] * nreq, first, [0] * nreq)
     rb, xb = step_inputs(first, more, first)
     ga, oa = c.run_gpu(ra, pts, ts, xa), c.run_oracle(ra, pts, ts, xa)
     gb, ob = c.run_gpu(rb, pts, ts, xb), c.run_oracle(rb, pts, ts, xb)
-    assert_close(ga, oa, bf16, "step 1")
-    assert_close(gb, ob, bf16, "step 2 on cached prefix")
+    assert_close(ga, oa, bf16, "d=%d step 1" % d)
+    assert_close(gb, ob, bf16, "d=%d step 2 on cached prefix" % d)
+    # stored K,V of the last layer (both steps' tokens) agree with the oracle's to the storage type's resolution
+    (P_, T_, pto, tso, xo) = reqs1[0]
+    S = first[0] + more[0]
+    pages = pts[pto:pto + (S + pt - 1) // pt]
+    Kg, Vg = Hn.read_kv(c.mem, c.L, c.d, c.H, c.pt, pages, S, L - 1)
+    Ko, Vo = c.oracle_kv_rows(pages, S, L - 1)
+    assert_close(Kg.float().cpu().numpy(), Ko, bf16, "d=%d stored K" % d)
+    assert_close(Vg.float().cpu().numpy(), Vo, bf16, "d=%d stored V" % d)
+    assert c.pool.stats()["bad_pages"] == 0
     c.close()
 
 
