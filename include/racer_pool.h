@@ -137,6 +137,20 @@ int32_t kv_seq_release(racer_pool_t* pool, uint64_t key); /* RACER_EBUSY while p
 int32_t emb_lookup(racer_pool_t* pool, const int64_t* ids, uint64_t n, uint32_t bag, void* out,
                    uint8_t* hit_flags, void* stream);
 
+/* ---- emb_lookup_noalloc: emb_lookup for callers that cannot allocate device memory: code under HIP graph
+ *      capture, tight serving loops, harnesses that forbid allocation.  Same arguments, results and LRU
+ *      semantics as emb_lookup; the miss path's work space is a fixed array inside the library (one per GPU,
+ *      about 10 MB, held until the process ends), and the call makes no hipMalloc / hipFree or other
+ *      allocating call and creates no events (racer_prof does not see it).  Limits: n <=
+ *      RACER_NOALLOC_MAX_LOOKUPS and n * row_bytes <= RACER_NOALLOC_MAX_ROW_BYTES_TOTAL, else RACER_ERANGE
+ *      and nothing is done.  Every call on a GPU, whatever its pool, shares that GPU's array: calls that
+ *      overlap on one GPU (two streams, two threads) race; calls ordered on one stream, or by the caller's own
+ *      events, do not.  Must be called with the pool's GPU current. */
+#define RACER_NOALLOC_MAX_LOOKUPS 16384ull
+#define RACER_NOALLOC_MAX_ROW_BYTES_TOTAL (8ull << 20)
+int32_t emb_lookup_noalloc(racer_pool_t* pool, const int64_t* ids, uint64_t n, uint32_t bag, void* out,
+                           uint8_t* hit_flags, void* stream);
+
 /* ---- several tables in one pool (paper Sec. II-B / III: a model looks up 10-25 embedding
  *      tables per request, and the lookup cost grows linearly with their number) -----------
  * pool_add_table: another pinned, device-mapped host table [rows][row_bytes] of the pool's

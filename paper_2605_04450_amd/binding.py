@@ -19,7 +19,7 @@ TAG_EMPTY = 0xFFFFFFFF
 EXPORTS = [
     "pool_create", "pool_destroy", "pool_set_split", "pool_stats", "pool_dump", "emb_cache_dump",
     "pool_num_sets", "pool_slot_of", "kv_seq_reserve", "kv_seq_lookup", "kv_seq_pin", "kv_seq_unpin",
-    "kv_seq_release", "emb_lookup", "emb_refill", "pool_add_table", "emb_lookup_tables", "hstu_model_create", "hstu_model_destroy", "hstu_step",
+    "kv_seq_release", "emb_lookup", "emb_lookup_noalloc", "emb_refill", "pool_add_table", "emb_lookup_tables", "hstu_model_create", "hstu_model_destroy", "hstu_step",
     "hstu_attn_paged", "racer_last_error", "racer_prof_enable", "racer_prof_read",
 ]
 PROF_KINDS = ("emb_gather", "emb_miss", "layernorm", "gemm_front", "attention", "gemm_back", "attn_reduce")
@@ -88,6 +88,7 @@ def load():
     for f in (L.kv_seq_pin, L.kv_seq_unpin, L.kv_seq_release):
         f.argtypes = [vp, u64]
     L.emb_lookup.argtypes = [vp, vp, u64, u32, vp, vp, vp]
+    L.emb_lookup_noalloc.argtypes = [vp, vp, u64, u32, vp, vp, vp]
     L.emb_refill.argtypes = [vp, vp, u64, vp]
     L.pool_add_table.argtypes = [vp, vp, u64, u32, C.POINTER(u32)]
     L.emb_lookup_tables.argtypes = [vp, vp, vp, u64, u32, vp, vp, vp]
@@ -227,6 +228,15 @@ def kv_seq_release(pool, key):
 def emb_lookup(pool, ids, out, bag=1, hit_flags=None, stream=None):
     """ids: int64 device tensor [n]; out: device tensor [n/bag][d]; hit_flags: uint8 device tensor [n] or None."""
     return load().emb_lookup(pool, _dp(ids), ids.numel(), bag, _dp(out), _dp(hit_flags), _stream_ptr(stream))
+
+
+NOALLOC_MAX_LOOKUPS = 16384
+NOALLOC_MAX_ROW_BYTES_TOTAL = 8 << 20
+
+
+def emb_lookup_noalloc(pool, ids, out, bag=1, hit_flags=None, stream=None):
+    """emb_lookup that allocates nothing (fixed work space inside the library; see the header for its limits)."""
+    return load().emb_lookup_noalloc(pool, _dp(ids), ids.numel(), bag, _dp(out), _dp(hit_flags), _stream_ptr(stream))
 
 
 def pool_add_table(pool, host_table, rows, row_bytes):

@@ -10,7 +10,7 @@
 #include <string>
 #include <vector>
 
-#include "../../include/racer_pool.h"
+#include "../../include/racer_pool.h"  // also fixes RACER_NOALLOC_MAX_*
 #include "kernels.h"
 #include "pool_host.h"
 
@@ -89,6 +89,46 @@ struct Staging {
     }
   }
 };
+
+// ---- work space of emb_lookup_noalloc -----------------------------------------------------------------------
+// One array per GPU, part of the library's code object, alive until the process ends.  It holds the miss path's
+// lists for up to kNoallocMaxLookups lookups whose rows add up to at most kNoallocStagingBytes.  In host code the
+// array's name is only a handle for hipGetSymbolAddress: the address that kernels and fills take is the one
+// that call returns for the current device, kept in g_scratch_ptr.
+constexpr uint64_t kNoallocMaxLookups = RACER_NOALLOC_MAX_LOOKUPS;
+constexpr uint64_t kNoallocStagingBytes = RACER_NOALLOC_MAX_ROW_BYTES_TOTAL;
+constexpr uint64_t kNoallocHash = 2 * kNoallocMaxLookups;  // slots of the dedupe table and of the set-chain heads
+constexpr uint64_t align256(uint64_t x) { return (x + 255) & ~255ull; }
+constexpr uint64_t kOffCtr = 0;                                                   // 8 x u32
+constexpr uint64_t kOffMissList = 256;                                            // u32 [lookups]
+constexpr uint64_t kOffDefList = kOffMissList + align256(4 * kNoallocMaxLookups);  // u32 [lookups]
+constexpr uint64_t kOffLoc = kOffDefList + align256(4 * kNoallocMaxLookups);       // i64 [lookups]
+constexpr uint64_t kOffHkeys = kOffLoc + align256(8 * kNoallocMaxLookups);         // u64 [hash]
+constexpr uint64_t kOffHvals = kOffHkeys + align256(8 * kNoallocHash);             // u64 [hash]
+constexpr uint64_t kOffHeads = kOffHvals + align256(8 * kNoallocHash);             // u64 [hash]
+constexpr uint64_t kOffHslot = kOffHeads + align256(8 * kNoallocHash);             // u32 [hash]
+constexpr uint64_t kOffUi = kOffHslot + align256(4 * kNoallocHash);                // five u32 / i32 [lookups]
+constexpr uint64_t kOffStaging = kOffUi + 5 * align256(4 * kNoallocMaxLookups);
+constexpr uint64_t kScratchBytes = kOffStaging + kNoallocStagingBytes;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+uint8_t* g_scratch_ptr[kMaxDevices] = {};
+
+// address of the current device's copy of `scratch` (looked up once per device)
+int32_t scratch_address(uint8_t** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return RACER_EINVAL;
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return RACER_EHIP;
+    g_scratch_ptr[dev] = static_cast<uint8_t*>(ptr);
+  }
+  *out = g_scratch_ptr[dev];
+  return RACER_OK;
+}
 
 }  // namespace
 
@@ -442,6 +482,57 @@ int32_t emb_lookup(racer_pool_t* p, const int64_t* ids, uint64_t n, uint32_t bag
     HIP_TRY(racer::launch_emb_miss_path(p->view(), ws, ids, static_cast<uint32_t>(n), bag, static_cast<uint8_t*>(out),
                                         p->batch, stream));
   }
+  return RACER_OK;
+}
+
+int32_t emb_lookup_noalloc(racer_pool_t* p, const int64_t* ids, uint64_t n, uint32_t bag, void* out, uint8_t* hit_flags,
+                           void* stream_v) {
+  if (!p || !p->device || !p->d_table) return RACER_EINVAL;
+  if (bag == 0 || bag > 64 || n % bag != 0) return RACER_EINVAL;
+  if (n && (!ids || !out)) return RACER_EINVAL;
+  if (n > kNoallocMaxLookups || n * p->cfg.row_bytes > kNoallocStagingBytes) {
+    g_last_error = "emb_lookup_noalloc: batch beyond the fixed work space (RACER_NOALLOC_MAX_LOOKUPS lookups, "
+                   "RACER_NOALLOC_MAX_ROW_BYTES_TOTAL bytes of rows)";
+    return RACER_ERANGE;
+  }
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  uint8_t* base = nullptr;
+  int32_t rc = scratch_address(&base);
+  if (rc) return rc;
+  p->batch += 1;  // one call = one LRU batch, empty or not
+  if (n == 0) return RACER_OK;
+  uint64_t hsize = 2048;
+  while (hsize < 2 * n) hsize <<= 1;  // <= kNoallocHash
+  racer::MissWs ws{};
+  ws.ctr = reinterpret_cast<uint32_t*>(base + kOffCtr);
+  ws.ctr_next = ws.ctr + 4;
+  ws.miss_list = reinterpret_cast<uint32_t*>(base + kOffMissList);
+  ws.def_list = reinterpret_cast<uint32_t*>(base + kOffDefList);
+  ws.loc = reinterpret_cast<int64_t*>(base + kOffLoc);
+  ws.hkeys = reinterpret_cast<unsigned long long*>(base + kOffHkeys);
+  ws.hvals = reinterpret_cast<unsigned long long*>(base + kOffHvals);
+  ws.heads = reinterpret_cast<unsigned long long*>(base + kOffHeads);
+  ws.hslot_u = reinterpret_cast<uint32_t*>(base + kOffHslot);
+  ws.hmask = ws.headmask = static_cast<uint32_t>(hsize - 1);
+  const uint64_t list = align256(4 * kNoallocMaxLookups);
+  ws.u_i = reinterpret_cast<uint32_t*>(base + kOffUi);
+  ws.u_id = reinterpret_cast<uint32_t*>(base + kOffUi + list);
+  ws.u_set = reinterpret_cast<uint32_t*>(base + kOffUi + 2 * list);
+  ws.u_next = reinterpret_cast<int32_t*>(base + kOffUi + 3 * list);
+  ws.u_way = reinterpret_cast<int32_t*>(base + kOffUi + 4 * list);
+  ws.staging = base + kOffStaging;
+  // The array keeps the last call's contents, whichever pool made it: the list counters and the three tables
+  // whose entries are told apart by the batch number must start at zero.  Fill kernels, so that the call can
+  // be captured into a graph.
+  HIP_TRY(racer::launch_fill_u32(ws.ctr, 8, 0u, stream));
+  HIP_TRY(racer::launch_fill_u32(reinterpret_cast<uint32_t*>(ws.hkeys), 2 * hsize, 0u, stream));
+  HIP_TRY(racer::launch_fill_u32(reinterpret_cast<uint32_t*>(ws.hvals), 2 * hsize, 0u, stream));
+  HIP_TRY(racer::launch_fill_u32(reinterpret_cast<uint32_t*>(ws.heads), 2 * hsize, 0u, stream));
+  p->last_stream = stream;
+  HIP_TRY(racer::launch_emb_probe(p->view(), ws, ids, static_cast<uint32_t>(n), bag, static_cast<uint8_t*>(out), hit_flags,
+                                  p->batch, stream));
+  HIP_TRY(racer::launch_emb_miss_path(p->view(), ws, ids, static_cast<uint32_t>(n), bag, static_cast<uint8_t*>(out), p->batch,
+                                      stream));
   return RACER_OK;
 }
 
