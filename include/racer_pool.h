@@ -62,6 +62,8 @@ typedef struct {
   uint64_t seqs_resident, seqs_evicted;
   uint64_t batch;        /* number of emb_lookup calls so far (the LRU clock) */
   uint64_t bad_pages;    /* page-table entries outside the pool seen by hstu kernels (skipped) */
+  uint64_t unordered_ts; /* requests of hstu calls whose timestamps decreased somewhere (served by the general time path) */
+  uint64_t ws_allocs;    /* (re)allocations of the library's work spaces so far; constant once pool_reserve covers the load */
 } racer_pool_stats;
 
 /* ---- pool (paper Sec. IV-B: one shared paged HBM space, movable logical EMB:KV boundary;
@@ -92,8 +94,25 @@ int32_t pool_destroy(racer_pool_t* pool);
  * removed ways move into vacated lower ways (device-to-device, enqueued on `stream`), the
  * tail pages return to the KV free list.  Resident KV pages never move and no host<->device
  * data copy is made.  Host metadata is final on return; `achieved` (host, may be NULL)
- * receives pages_emb / pages. */
+ * receives pages_emb / pages.  If the device half cannot be queued (RACER_EHIP, RACER_ENOMEM)
+ * the host metadata is put back as it was: the split, the page owners and the resident
+ * sequences are those from before the call. */
 int32_t pool_set_split(racer_pool_t* pool, double emb_frac, void* stream, double* achieved);
+
+/* pool_reserve: size the library's work spaces once.  The miss path's lists, the step's activation matrices,
+ * work lists, partial outputs, pinned staging buffers and the step's streams otherwise grow on demand, and a
+ * growth (hipFree + hipMalloc, after waiting for the streams that use the old buffer) stalls the device in the
+ * middle of serving.  After pool_reserve, no call whose sizes stay within *r allocates (pool_stats.ws_allocs
+ * stays constant).  model (may be NULL: EMB calls only) fixes width, heads, element type and page tokens of the
+ * steps to come.  A later call beyond the reserved sizes still works and grows what it needs.
+ * Errors: RACER_EINVAL (metadata-only pool, sizes out of range), RACER_EHIP / RACER_ENOMEM. */
+typedef struct {
+  uint64_t max_lookups;    /* ids per emb_lookup / emb_lookup_tables / emb_refill call; 0: none */
+  uint32_t max_requests;   /* requests per hstu_step / hstu_attn_paged call; 0: none */
+  uint64_t max_new_tokens; /* sum of new_len over the requests of one call */
+  uint32_t max_seq_tokens; /* largest prefix_len + new_len of a request */
+} racer_reserve;
+int32_t pool_reserve(racer_pool_t* pool, const racer_hstu_t* model, const racer_reserve* r, void* stream);
 
 /* pool_stats: waits for the pool's last stream, then fills *out (host). */
 int32_t pool_stats(racer_pool_t* pool, racer_pool_stats* out);
@@ -223,7 +242,9 @@ int32_t hstu_model_destroy(racer_hstu_t* model);
 /* hstu_step: all L layers for B requests.  reqs (host) [B]; kv_page_tables (dev) int32,
  * n_page_entries long, request r using ceil((prefix+new)/page_tokens) entries from its
  * offset; x_in (dev) [N][d] new-token inputs (N = sum new_len); ts (dev) int64 seconds,
- * non-decreasing per request; out (dev) [N][d].  For every layer the new tokens' K,V are
+ * normally non-decreasing per request (a request whose timestamps decrease somewhere is
+ * served all the same, by a slower path in which a negative gap falls into bucket 0, and
+ * counted in pool_stats.unordered_ts); out (dev) [N][d].  For every layer the new tokens' K,V are
  * written into the request's pages at positions prefix_len.., then every new token attends
  * to positions 0..its own through the page table.  Page ids outside the pool are skipped
  * and counted in bad_pages.  The work is ordered on `stream` as usual: what the caller

@@ -17,7 +17,7 @@ ELEM_F32, ELEM_BF16 = 0, 1
 TAG_EMPTY = 0xFFFFFFFF
 
 EXPORTS = [
-    "pool_create", "pool_destroy", "pool_set_split", "pool_stats", "pool_dump", "emb_cache_dump",
+    "pool_create", "pool_destroy", "pool_set_split", "pool_reserve", "pool_stats", "pool_dump", "emb_cache_dump",
     "pool_num_sets", "pool_slot_of", "kv_seq_reserve", "kv_seq_lookup", "kv_seq_pin", "kv_seq_unpin",
     "kv_seq_release", "emb_lookup", "emb_lookup_noalloc", "emb_refill", "pool_add_table", "emb_lookup_tables", "hstu_model_create", "hstu_model_destroy", "hstu_step",
     "hstu_attn_paged", "racer_last_error", "racer_prof_enable", "racer_prof_read",
@@ -39,10 +39,15 @@ class PoolStats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in (
         "lookups", "hits", "misses", "unique_misses", "inserted", "evicted", "bypassed", "invalid_ids",
         "shrink_evicted", "shrink_moved", "pages_total", "pages_emb", "pages_kv_used", "pages_kv_free",
-        "seqs_resident", "seqs_evicted", "batch", "bad_pages")]
+        "seqs_resident", "seqs_evicted", "batch", "bad_pages", "unordered_ts", "ws_allocs")]
 
     def asdict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
+class Reserve(C.Structure):
+    _fields_ = [("max_lookups", C.c_uint64), ("max_requests", C.c_uint32), ("max_new_tokens", C.c_uint64),
+                ("max_seq_tokens", C.c_uint32)]
 
 
 class HstuCfg(C.Structure):
@@ -87,6 +92,7 @@ def load():
     L.kv_seq_lookup.argtypes = [vp, u64, C.POINTER(u32), vp, u32, C.POINTER(u32)]
     for f in (L.kv_seq_pin, L.kv_seq_unpin, L.kv_seq_release):
         f.argtypes = [vp, u64]
+    L.pool_reserve.argtypes = [vp, vp, C.POINTER(Reserve), vp]
     L.emb_lookup.argtypes = [vp, vp, u64, u32, vp, vp, vp]
     L.emb_lookup_noalloc.argtypes = [vp, vp, u64, u32, vp, vp, vp]
     L.emb_refill.argtypes = [vp, vp, u64, vp]
@@ -157,6 +163,12 @@ def pool_set_split(pool, emb_frac, stream=None, device=True):
     ach = C.c_double(0.0)
     rc = load().pool_set_split(pool, float(emb_frac), _stream_ptr(stream) if device else None, C.byref(ach))
     return rc, ach.value
+
+
+def pool_reserve(pool, model, max_lookups=0, max_requests=0, max_new_tokens=0, max_seq_tokens=0, stream=None):
+    """Size the library's work spaces ahead of time (model: handle or None)."""
+    r = Reserve(max_lookups, max_requests, max_new_tokens, max_seq_tokens)
+    return load().pool_reserve(pool, model, C.byref(r), _stream_ptr(stream))
 
 
 def pool_stats(pool):

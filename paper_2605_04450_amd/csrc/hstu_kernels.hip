@@ -814,8 +814,8 @@ __global__ __launch_bounds__(256) void attention_f32(HstuDims hd, uint32_t layer
 }
 
 // ---------------------------------------------------------------------------------------
-// bf16 paged attention on MFMA, d_h = 64.  A block of four wavefronts owns 256 consecutive
-// queries of one request and one head (64 per wavefront, as two 32-query groups) and walks
+// bf16 paged attention on MFMA, d_h = 64.  A block of four wavefronts owns 128 * NQB consecutive
+// queries of one request and one head (32 * NQB per wavefront, as NQB 32-query groups) and walks
 // a range of key tiles (64 keys), staging K [key][d_h] and V^T [d_h][key] of the tile in
 // LDS through the page table (tile k+1 is fetched into registers while tile k is used).
 // Each wavefront computes S^T = K Q^T (keys x queries, so a lane ends up holding one query
@@ -906,7 +906,8 @@ __global__ __launch_bounds__(256, NQB == 1 ? 3 : 2) void attention_bf16_mfma(Hst
   const long long* tsr = ts + rq.ts_off;
   const long long ts_base = tsr[0];
   const long long span = tsr[S - 1] - ts_base;
-  const bool fast = hd.n_time <= 32 && span >= 0 && span < (1ll << 31);
+  // 32-bit times relative to the request's first: only for requests whose timestamps never decrease
+  const bool fast = hd.n_time <= 32 && rq.ts_ordered != 0 && span >= 0 && span < (1ll << 31);
   if (tid < 64) sm.time[tid] = tid < hd.n_time ? time[(static_cast<uint64_t>(layer) * hd.H + h) * hd.n_time + tid] : 0.0f;
   if (tid >= 64 && tid < 96) {
     const uint32_t bkt = 95 - tid;  // floor(log2(gap)) of a gap with tid - 64 leading zeros
@@ -1326,6 +1327,24 @@ __global__ __launch_bounds__(256) void attention_reduce(HstuDims hd, uint32_t q_
   *reinterpret_cast<uint2*>(o + static_cast<uint64_t>(rq.x_off + qi) * hd.d + h * 64 + 4 * c4) = w;
 }
 
+// One wavefront per request: are its timestamps non-decreasing?
+__global__ __launch_bounds__(256) void check_timestamps(ReqDev* __restrict__ reqs, uint32_t B,
+                                                        const long long* __restrict__ ts,
+                                                        unsigned long long* __restrict__ counters) {
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= B) return;
+  const uint32_t S = reqs[r].prefix_len + reqs[r].new_len;
+  const long long* t = ts + reqs[r].ts_off;
+  bool bad = false;
+  for (uint32_t j = 1 + lane; j < S; j += 64) bad |= t[j] < t[j - 1];
+  const bool any_bad = __ballot(bad) != 0;
+  if (lane == 0) {
+    reqs[r].ts_ordered = any_bad ? 0u : 1u;
+    if (any_bad) atomicAdd(&counters[ctr_index(kCtrUnorderedTs)], 1ull);
+  }
+}
+
 __global__ void scale_f32(const float* __restrict__ in, float* __restrict__ out, uint64_t n, float s) {
   for (uint64_t k = blockIdx.x * static_cast<uint64_t>(blockDim.x) + threadIdx.x; k < n;
        k += static_cast<uint64_t>(gridDim.x) * blockDim.x)
@@ -1489,6 +1508,14 @@ hipError_t launch_attention_reduce(const HstuDims& hd, const StepLists& sl, void
   if (hd.elem != 1 || sl.n_groups == 0) return hipSuccess;
   hipLaunchKernelGGL(attention_reduce, dim3(sl.n_groups * hd.H, (sl.q_block * 16 + 255) / 256), dim3(256), 0, stream, hd,
                      sl.q_block, sl.reqs, sl.groups, sl.partials, static_cast<uint16_t*>(o));
+  return hipGetLastError();
+}
+
+hipError_t launch_check_timestamps(ReqDev* reqs, uint32_t B, const int64_t* ts, unsigned long long* counters,
+                                   hipStream_t stream) {
+  if (B == 0) return hipSuccess;
+  hipLaunchKernelGGL(check_timestamps, dim3((B + 3) / 4), dim3(256), 0, stream, reqs, B,
+                     reinterpret_cast<const long long*>(ts), counters);
   return hipGetLastError();
 }
 

@@ -9,7 +9,7 @@ namespace racer {
 // Device counters (unsigned long long each)
 enum Counter : int {
   kCtrLookups = 0, kCtrHits, kCtrMisses, kCtrUnique, kCtrInserted, kCtrEvicted, kCtrBypassed,
-  kCtrInvalid, kCtrShrinkEvicted, kCtrShrinkMoved, kCtrBadPages, kCtrCount
+  kCtrInvalid, kCtrShrinkEvicted, kCtrShrinkMoved, kCtrBadPages, kCtrUnorderedTs, kCtrCount
 };
 
 // The counters exist in kCtrShards copies; a block adds to the copy chosen by its index so that
@@ -101,7 +101,8 @@ struct HstuDims {
 
 struct ReqDev {  // device copy of one request
   uint32_t prefix_len, new_len;
-  uint32_t page_table_off, ts_off, x_off, pad;
+  uint32_t page_table_off, ts_off, x_off;
+  uint32_t ts_ordered;  // written by the timestamp check: 1 if the request's timestamps never decrease
 };
 
 struct KvView {
@@ -157,6 +158,13 @@ struct StepLists {
   uint32_t q_block;          // queries per item
   uint32_t B, N;
 };
+
+// One pass over every request's timestamps: ts_ordered of each request, and the number of requests whose
+// timestamps decrease somewhere added to the kCtrUnorderedTs counter.  The attention kernels take their 32-bit
+// relative-time paths only for ordered requests (an unordered one gets the general 64-bit gaps, where a negative gap
+// falls into bucket 0).
+hipError_t launch_check_timestamps(ReqDev* reqs, uint32_t B, const int64_t* ts, unsigned long long* counters,
+                                   hipStream_t stream);
 
 hipError_t launch_layernorm(const HstuDims& hd, const void* x, const float* g, const float* b,
                             const void* gate /*nullable: multiply by gate rows*/, void* y, uint32_t N,

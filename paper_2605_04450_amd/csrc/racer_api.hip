@@ -5,7 +5,9 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <string>
 #include <vector>
@@ -31,6 +33,16 @@ int32_t hip_fail(hipError_t e, const char* what) {
 
 bool is_pow2(uint64_t x) { return x && !(x & (x - 1)); }
 
+// Tests of the error paths name the call that is to fail once in the environment (RACER_FAULT_INJECT=split); the
+// variable is cleared by the call that honours it.  Nothing on the GPU is made to fail: the call returns before it
+// queues its device work.
+bool fault_injected(const char* what) {
+  const char* v = std::getenv("RACER_FAULT_INJECT");
+  if (!v || std::strcmp(v, what) != 0) return false;
+  unsetenv("RACER_FAULT_INJECT");
+  return true;
+}
+
 // Device memory for metadata and workspaces.  With `zero` the memory is cleared by a fill kernel on `stream`,
 // the stream whose later kernels use it (a clear on the null stream is not ordered with a non-blocking stream).
 template <typename T>
@@ -51,6 +63,26 @@ struct Staging {
   uint64_t cap[2] = {0, 0};
   bool pending[2] = {false, false};
   int next = 0;
+  uint64_t allocs = 0;  // pinned (re)allocations so far
+
+  // both buffers at least `bytes` large, so that no later acquire of up to that size allocates
+  int32_t reserve(uint64_t bytes) {
+    for (int k = 0; k < 2; ++k) {
+      if (!done[k]) HIP_TRY(hipEventCreateWithFlags(&done[k], hipEventDisableTiming));
+      if (cap[k] >= bytes) continue;
+      if (pending[k]) {
+        HIP_TRY(hipEventSynchronize(done[k]));
+        pending[k] = false;
+      }
+      if (buf[k]) HIP_TRY(hipHostFree(buf[k]));
+      buf[k] = nullptr;
+      cap[k] = 0;
+      HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&buf[k]), bytes, hipHostMallocDefault));
+      cap[k] = bytes;
+      ++allocs;
+    }
+    return RACER_OK;
+  }
 
   int32_t acquire(uint64_t bytes, uint8_t** out, int* which) {
     const int k = next;
@@ -66,6 +98,7 @@ struct Staging {
       const uint64_t want = std::max<uint64_t>(bytes * 2, 1 << 16);
       HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&buf[k]), want, hipHostMallocDefault));
       cap[k] = want;
+      ++allocs;
     }
     if (!done[k]) HIP_TRY(hipEventCreateWithFlags(&done[k], hipEventDisableTiming));
     *out = buf[k];
@@ -150,6 +183,7 @@ struct racer_pool {
   uint64_t gid_cap = 0;
   Staging stage;
   uint32_t batch = 0;
+  uint64_t ws_allocs = 0;  // device work-space (re)allocations so far (pool_reserve keeps later calls from adding any)
   uint64_t launches = 0;  // emb_lookup calls that reached the device (selects the list-counter parity)
   hipStream_t last_stream = nullptr;
   // miss-path workspace, grown on demand
@@ -157,7 +191,7 @@ struct racer_pool {
   uint32_t* ws_ctr = nullptr;
   racer::MissWs ws{};
   // hstu workspace
-  uint64_t hw_rows = 0, hw_d = 0, hw_esize = 0;
+  uint64_t hw_slot = 0;  // bytes of each of the six activation matrices of a step
   uint8_t* hw_buf = nullptr;
   uint64_t hl_cap = 0;
   uint8_t* hl_dev = nullptr;
@@ -255,6 +289,7 @@ int32_t ensure_miss_ws(racer_pool* p, uint64_t n, hipStream_t stream) {
   const uint64_t cap = std::max<uint64_t>(n, 1024);
   uint64_t hsize = 2048;
   while (hsize < 2 * cap) hsize <<= 1;
+  p->ws_allocs += 1;
   racer::MissWs& w = p->ws;
   int32_t rc;
   if ((rc = dev_alloc(&p->ws_ctr, 8, true, stream))) return rc;
@@ -274,6 +309,72 @@ int32_t ensure_miss_ws(racer_pool* p, uint64_t n, hipStream_t stream) {
   w.hmask = static_cast<uint32_t>(hsize - 1);
   w.headmask = static_cast<uint32_t>(hsize - 1);
   p->ws_cap = cap;
+  return RACER_OK;
+}
+
+
+// The remaining work spaces grow on demand (a growth waits for the streams that may still use the old buffer);
+// pool_reserve sizes them all ahead of time.
+int32_t ensure_gid(racer_pool* p, uint64_t n) {  // global ids of a multi-table lookup
+  if (n <= p->gid_cap) return RACER_OK;
+  HIP_TRY(hipStreamSynchronize(p->last_stream));
+  if (p->gid_buf) HIP_TRY(hipFree(p->gid_buf));
+  p->gid_buf = nullptr;
+  p->gid_cap = 0;
+  const uint64_t cap = std::max<uint64_t>(n, 1024);
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->gid_buf), cap * sizeof(int64_t)));
+  p->gid_cap = cap;
+  p->ws_allocs += 1;
+  return RACER_OK;
+}
+
+int32_t ensure_partials(racer_pool* p, uint64_t bytes, hipStream_t stream) {  // fp32 partials of split attention items
+  if (bytes <= p->hp_cap) return RACER_OK;
+  HIP_TRY(hipStreamSynchronize(p->last_stream));
+  HIP_TRY(hipStreamSynchronize(stream));
+  if (p->hp_dev) HIP_TRY(hipFree(p->hp_dev));
+  p->hp_dev = nullptr;
+  p->hp_cap = 0;
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->hp_dev), bytes));
+  p->hp_cap = bytes;
+  p->ws_allocs += 1;
+  return RACER_OK;
+}
+
+int32_t ensure_lists(racer_pool* p, uint64_t need, uint64_t want) {  // device copy of a step's host-built lists
+  if (need <= p->hl_cap) return RACER_OK;
+  HIP_TRY(hipStreamSynchronize(p->last_stream));
+  if (p->hl_dev) HIP_TRY(hipFree(p->hl_dev));
+  p->hl_dev = nullptr;
+  p->hl_cap = 0;
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->hl_dev), want));
+  p->hl_cap = want;
+  p->ws_allocs += 1;
+  return RACER_OK;
+}
+
+// Activation work space of a step: six matrices (xn, u, q, o and two layer buffers) of `slot` bytes each.
+int32_t ensure_hstu_ws(racer_pool* p, uint64_t slot, hipStream_t stream) {
+  if (slot <= p->hw_slot) return RACER_OK;
+  HIP_TRY(hipStreamSynchronize(stream));
+  HIP_TRY(hipStreamSynchronize(p->last_stream));
+  if (p->hw_buf) HIP_TRY(hipFree(p->hw_buf));
+  p->hw_buf = nullptr;
+  p->hw_slot = 0;
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->hw_buf), slot * 6));
+  p->hw_slot = slot;
+  p->ws_allocs += 1;
+  return RACER_OK;
+}
+
+// The step's further streams and its fork / join events.
+int32_t ensure_step_streams(racer_pool* p, uint32_t n_aux) {
+  if (!p->ev_fork) HIP_TRY(hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming));
+  for (uint32_t k = 0; k < n_aux; ++k) {
+    if (p->aux_stream[k]) continue;
+    HIP_TRY(hipStreamCreateWithFlags(&p->aux_stream[k], hipStreamNonBlocking));
+    HIP_TRY(hipEventCreateWithFlags(&p->ev_join[k], hipEventDisableTiming));
+  }
   return RACER_OK;
 }
 
@@ -371,27 +472,41 @@ int32_t pool_set_split(racer_pool_t* p, double emb_frac, void* stream_v, double*
   if (!p) return RACER_EINVAL;
   hipStream_t stream = static_cast<hipStream_t>(stream_v);
   const uint64_t G = p->host.layer_pages();
+  // The host bookkeeping changes first (the device half needs its result); a copy of it is kept until the device
+  // half has been queued, and put back if that fails, so that host and device never disagree about the EMB pages.
+  std::unique_ptr<racer::HostPool> undo;
+  if (p->device) undo.reset(new (std::nothrow) racer::HostPool(p->host));
+  if (p->device && !undo) return RACER_ENOMEM;
   const racer::SplitPlan plan = p->host.set_split(emb_frac);
   if (plan.rc < 0) return plan.rc;
-  if (achieved) *achieved = static_cast<double>(p->host.n_emb()) / static_cast<double>(p->host.n_pages());
+  int32_t rc = RACER_OK;
   if (p->device && plan.new_emb != plan.old_emb) {
-    p->last_stream = stream;
-    if (plan.new_emb > plan.old_emb) {
-      // newly mapped logical pages: ship their physical ids; the new ways are already empty
-      const uint64_t count = plan.new_emb - plan.old_emb;
-      uint8_t* buf;
-      int which;
-      int32_t rc = p->stage.acquire(count * sizeof(int32_t), &buf, &which);
-      if (rc) return rc;
-      std::memcpy(buf, p->host.emb_pages().data() + plan.old_emb, count * sizeof(int32_t));
-      HIP_TRY(hipMemcpyAsync(p->d_emb_pages + plan.old_emb, buf, count * sizeof(int32_t), hipMemcpyHostToDevice, stream));
-      if ((rc = p->stage.mark(which, stream))) return rc;
-    } else {
+    rc = [&]() -> int32_t {
+      if (fault_injected("split")) return hip_fail(hipErrorUnknown, "pool_set_split (injected fault)");
+      if (plan.new_emb > plan.old_emb) {
+        // newly mapped logical pages: ship their physical ids; the new ways are already empty
+        const uint64_t count = plan.new_emb - plan.old_emb;
+        uint8_t* buf;
+        int which;
+        int32_t r = p->stage.acquire(count * sizeof(int32_t), &buf, &which);
+        if (r) return r;
+        std::memcpy(buf, p->host.emb_pages().data() + plan.old_emb, count * sizeof(int32_t));
+        HIP_TRY(hipMemcpyAsync(p->d_emb_pages + plan.old_emb, buf, count * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+        return p->stage.mark(which, stream);
+      }
       const uint32_t old_full = static_cast<uint32_t>(plan.old_emb / G);
       const uint32_t old_part = static_cast<uint32_t>((plan.old_emb % G) * p->host.spp());
       HIP_TRY(racer::launch_emb_shrink(p->view(), old_full, old_part, stream));
+      return RACER_OK;
+    }();
+    if (rc) {
+      p->host = std::move(*undo);  // nothing has changed: the device still holds the old split's state
+      if (achieved) *achieved = static_cast<double>(p->host.n_emb()) / static_cast<double>(p->host.n_pages());
+      return rc;
     }
+    p->last_stream = stream;
   }
+  if (achieved) *achieved = static_cast<double>(p->host.n_emb()) / static_cast<double>(p->host.n_pages());
   return plan.rc;
 }
 
@@ -416,7 +531,9 @@ int32_t pool_stats(racer_pool_t* p, racer_pool_stats* out) {
     out->shrink_evicted = c[racer::kCtrShrinkEvicted];
     out->shrink_moved = c[racer::kCtrShrinkMoved];
     out->bad_pages = c[racer::kCtrBadPages];
+    out->unordered_ts = c[racer::kCtrUnorderedTs];
   }
+  out->ws_allocs = p->ws_allocs + p->stage.allocs + p->hstage.allocs;
   out->pages_total = p->host.n_pages();
   out->pages_emb = p->host.n_emb();
   out->pages_kv_free = p->host.free_count();
@@ -568,15 +685,8 @@ int32_t emb_lookup_tables(racer_pool_t* p, const uint32_t* table_of, const int64
   if (n >= 0xFFFFFFFFull || (n && (!table_of || !ids))) return RACER_EINVAL;
   if (p->tables.size() < 2) return RACER_EINVAL;  // one table: emb_lookup
   hipStream_t stream = static_cast<hipStream_t>(stream_v);
-  if (n > p->gid_cap) {
-    HIP_TRY(hipStreamSynchronize(p->last_stream));
-    if (p->gid_buf) HIP_TRY(hipFree(p->gid_buf));
-    p->gid_buf = nullptr;
-    p->gid_cap = 0;
-    const uint64_t cap = std::max<uint64_t>(n, 1024);
-    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->gid_buf), cap * sizeof(int64_t)));
-    p->gid_cap = cap;
-  }
+  int32_t rc_g = ensure_gid(p, n);
+  if (rc_g) return rc_g;
   HIP_TRY(racer::launch_emb_global_ids(p->view(), table_of, ids, static_cast<uint32_t>(n), p->gid_buf, stream));
   return emb_lookup(p, p->gid_buf, n, bag, out, hit_flags, stream_v);
 }
@@ -680,6 +790,25 @@ constexpr uint32_t kMaxRuns = 4;
 constexpr uint32_t kStepRuns = RACER_STEP_RUNS;  // pipelines of a large step
 static_assert(kStepRuns >= 2 && kStepRuns <= kMaxRuns, "pipelines per step");
 
+// Upper bounds of a step's list bytes and partial-output bytes for up to B requests, N new tokens and sequences of up
+// to max_seq tokens (pool_reserve sizes the work spaces with them; prepare_step's own sizes never exceed them).
+// Q query tiles (128 new tokens of one request), V visits of 64-key tiles; a query tile is cut into at most
+// n_kt / chunk + 1 items, and the chunk is at least V * H / 2048 tiles unless the item's page-table slice caps it.
+struct StepBounds { uint64_t list_bytes, partial_bytes; };
+StepBounds step_bounds(uint64_t B, uint64_t N, uint64_t max_seq, uint32_t H, uint32_t page_tokens) {
+  const uint64_t Q = N / 128 + B;
+  const uint64_t V = Q * (max_seq / 64 + 1);
+  const uint64_t chunk_cap = std::max<uint64_t>(1, (static_cast<uint64_t>(racer::kAttnMaxItemPages) - 2) * page_tokens / 64 * 4 / 5);
+  const uint64_t items = Q + std::max<uint64_t>(2048 / H + 1, V / chunk_cap + 1);
+  StepBounds b;
+  b.list_bytes = sizeof(racer::ReqDev) * (B + 1) + 4 * (N + 1) + sizeof(racer::AttnItem) * items +
+                 (sizeof(racer::AttnGroup) + sizeof(racer::RowTile)) * (Q + 1) +
+                 sizeof(racer::AttnWork) * racer::kXcds * items * H + 6 * 256;
+  b.partial_bytes = items * H * 128 * 64 * sizeof(float);
+  b.partial_bytes += b.partial_bytes / 4;
+  return b;
+}
+
 struct StepCtx {
   racer::HstuDims hd;
   racer::KvView kv;
@@ -695,7 +824,7 @@ struct StepCtx {
 // equal attention work, each with its own work list, groups and row tiles (pipelines that touch disjoint rows,
 // pages and partial slots), if it has at least as many requests as pipelines.
 int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, uint32_t B, uint64_t n_page_entries,
-                     hipStream_t stream, StepCtx* ctx, bool want_split = false) {
+                     const int64_t* ts, hipStream_t stream, StepCtx* ctx, bool want_split = false) {
   const racer_hstu_cfg& c = m->cfg;
   if (!p->device || c.page_tokens != p->cfg.page_tokens || c.elem != p->cfg.elem) return RACER_EINVAL;
   const uint64_t esize = c.elem == RACER_ELEM_BF16 ? 2 : 4;
@@ -824,14 +953,9 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   }
   work_begin[n_runs] = work.size();
   const uint64_t partial_bytes = static_cast<uint64_t>(n_slots) * c.H * q_block * 64 * sizeof(float);
-  if (partial_bytes > p->hp_cap) {
-    HIP_TRY(hipStreamSynchronize(p->last_stream));
-    HIP_TRY(hipStreamSynchronize(stream));
-    if (p->hp_dev) HIP_TRY(hipFree(p->hp_dev));
-    p->hp_dev = nullptr;
-    p->hp_cap = 0;
-    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->hp_dev), partial_bytes + partial_bytes / 4));
-    p->hp_cap = partial_bytes + partial_bytes / 4;
+  {
+    int32_t rc_p = ensure_partials(p, partial_bytes + partial_bytes / 4, stream);
+    if (rc_p) return rc_p;
   }
 
   const uint64_t bytes_reqs = sizeof(racer::ReqDev) * std::max<uint32_t>(B, 1);
@@ -849,13 +973,9 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   const uint64_t off_row_tiles = (off_groups + bytes_groups + 255) & ~255ull;
   const uint64_t off_work = (off_row_tiles + bytes_row_tiles + 255) & ~255ull;
   const uint64_t total = off_work + bytes_work;
-  if (total > p->hl_cap) {
-    HIP_TRY(hipStreamSynchronize(p->last_stream));
-    if (p->hl_dev) HIP_TRY(hipFree(p->hl_dev));
-    p->hl_dev = nullptr;
-    p->hl_cap = 0;
-    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->hl_dev), total * 2));
-    p->hl_cap = total * 2;
+  {
+    int32_t rc_l = ensure_lists(p, total, total * 2);
+    if (rc_l) return rc_l;
   }
   uint8_t* hbuf;
   int which;
@@ -865,7 +985,7 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   uint32_t* hrow = reinterpret_cast<uint32_t*>(hbuf + off_rows);
   for (uint32_t r = 0; r < B; ++r) {
     hr[r] = racer::ReqDev{reqs[r].prefix_len, reqs[r].new_len, static_cast<uint32_t>(reqs[r].page_table_off),
-                          static_cast<uint32_t>(reqs[r].ts_off), static_cast<uint32_t>(reqs[r].x_off), 0};
+                          static_cast<uint32_t>(reqs[r].ts_off), static_cast<uint32_t>(reqs[r].x_off), 0 /* set by the check */};
     for (uint32_t i = 0; i < reqs[r].new_len; ++i) hrow[reqs[r].x_off + i] = r;
   }
   if (!items.empty()) std::memcpy(hbuf + off_items, items.data(), sizeof(racer::AttnItem) * items.size());
@@ -874,6 +994,8 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   if (!work.empty()) std::memcpy(hbuf + off_work, work.data(), sizeof(racer::AttnWork) * work.size());
   HIP_TRY(hipMemcpyAsync(p->hl_dev, hbuf, total, hipMemcpyHostToDevice, stream));
   if ((rc = p->hstage.mark(which, stream))) return rc;
+  // which requests' timestamps never decrease (the attention kernels' 32-bit time paths rely on it)
+  if (ts && N) HIP_TRY(racer::launch_check_timestamps(reinterpret_cast<racer::ReqDev*>(p->hl_dev), B, ts, p->d_counters, stream));
 
   ctx->esize = esize;
   uint32_t pt_shift = 32;
@@ -919,25 +1041,33 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   return RACER_OK;
 }
 
-// Activation workspace of a step: six [rows][d] matrices (xn, u, q, o and two layer buffers).
-int32_t ensure_hstu_ws(racer_pool* p, uint64_t N, uint64_t d, uint64_t esize, hipStream_t stream) {
-  if (p->hw_rows >= N && p->hw_d == d && p->hw_esize == esize) return RACER_OK;
-  HIP_TRY(hipStreamSynchronize(stream));
-  HIP_TRY(hipStreamSynchronize(p->last_stream));
-  if (p->hw_buf) HIP_TRY(hipFree(p->hw_buf));
-  p->hw_buf = nullptr;
-  p->hw_rows = 0;
-  const uint64_t slot = (N * d * esize + 255) & ~255ull;
-  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&p->hw_buf), slot * 6));
-  p->hw_rows = N;
-  p->hw_d = d;
-  p->hw_esize = esize;
-  return RACER_OK;
-}
-
 }  // namespace
 
 extern "C" {
+
+int32_t pool_reserve(racer_pool_t* p, const racer_hstu_t* m, const racer_reserve* r, void* stream_v) {
+  if (!p || !r || !p->device) return RACER_EINVAL;
+  hipStream_t stream = static_cast<hipStream_t>(stream_v);
+  int32_t rc;
+  if ((rc = p->stage.reserve(p->host.n_pages() * sizeof(int32_t)))) return rc;  // the largest growth a split change can ship
+  if (r->max_lookups) {
+    if (r->max_lookups >= 0xFFFFFFFFull) return RACER_EINVAL;
+    if ((rc = ensure_miss_ws(p, r->max_lookups, stream))) return rc;
+    if ((rc = ensure_gid(p, r->max_lookups))) return rc;
+  }
+  if (m && r->max_requests) {
+    const racer_hstu_cfg& c = m->cfg;
+    if (r->max_new_tokens >= (1ull << 31) || r->max_seq_tokens == 0) return RACER_EINVAL;
+    const uint64_t esize = c.elem == RACER_ELEM_BF16 ? 2 : 4;
+    const StepBounds b = step_bounds(r->max_requests, r->max_new_tokens, r->max_seq_tokens, c.H, c.page_tokens);
+    if ((rc = ensure_lists(p, b.list_bytes, b.list_bytes))) return rc;
+    if ((rc = p->hstage.reserve(b.list_bytes))) return rc;
+    if (c.elem == RACER_ELEM_BF16 && (rc = ensure_partials(p, b.partial_bytes, stream))) return rc;
+    if ((rc = ensure_hstu_ws(p, (r->max_new_tokens * c.d * esize + 255) & ~255ull, stream))) return rc;
+    if ((rc = ensure_step_streams(p, kStepRuns - 1))) return rc;
+  }
+  return RACER_OK;
+}
 
 int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, uint32_t B, const int32_t* page_tables,
                   uint64_t n_page_entries, const void* x_in, const int64_t* ts, void* out, void* stream_v) {
@@ -956,15 +1086,15 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
   const bool want_split = c.elem == RACER_ELEM_BF16 && !p->prof_on && B >= 2 &&
                           (n_tokens >= kSplitMinTokens || n_pairs >= kSplitMinPairs);
   StepCtx ctx;
-  int32_t rc = prepare_step(p, m, reqs, B, n_page_entries, stream, &ctx, want_split);
+  int32_t rc = prepare_step(p, m, reqs, B, n_page_entries, ts, stream, &ctx, want_split);
   if (rc) return rc;
   p->last_stream = stream;
   const uint32_t N = ctx.sl.N;
   if (N == 0) return RACER_OK;
   if (!page_tables || !x_in || !ts || !out) return RACER_EINVAL;
   const uint64_t d = c.d;
-  if ((rc = ensure_hstu_ws(p, N, d, ctx.esize, stream))) return rc;
-  const uint64_t stride = ((static_cast<uint64_t>(p->hw_rows) * d * ctx.esize) + 255) & ~255ull;
+  if ((rc = ensure_hstu_ws(p, (static_cast<uint64_t>(N) * d * ctx.esize + 255) & ~255ull, stream))) return rc;
+  const uint64_t stride = p->hw_slot;
   uint8_t* xn = p->hw_buf;
   uint8_t* u = xn + stride;
   uint8_t* q = u + stride;
@@ -977,15 +1107,9 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
   for (uint32_t run = 0; split && run < n_runs; ++run)
     if (ctx.run[run].n_row_tiles == 0 || ctx.run[run].n_work == 0) split = false;  // a run without new tokens
   if (split) {  // the other pipelines start behind everything the caller's stream holds so far (lists included)
-    if (!p->ev_fork) HIP_TRY(hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming));
+    if ((rc = ensure_step_streams(p, n_runs - 1))) return rc;
     HIP_TRY(hipEventRecord(p->ev_fork, stream));
-    for (uint32_t k = 0; k + 1 < n_runs; ++k) {
-      if (!p->aux_stream[k]) {
-        HIP_TRY(hipStreamCreateWithFlags(&p->aux_stream[k], hipStreamNonBlocking));
-        HIP_TRY(hipEventCreateWithFlags(&p->ev_join[k], hipEventDisableTiming));
-      }
-      HIP_TRY(hipStreamWaitEvent(p->aux_stream[k], p->ev_fork, 0));
-    }
+    for (uint32_t k = 0; k + 1 < n_runs; ++k) HIP_TRY(hipStreamWaitEvent(p->aux_stream[k], p->ev_fork, 0));
   }
   // one layer of one pipeline: rows, pages and partial slots of `sl` only
   auto layer_of = [&](const racer::StepLists& sl, uint32_t row0, uint32_t rows, hipStream_t st, uint32_t l,
@@ -1064,15 +1188,15 @@ int32_t hstu_attn_paged(racer_pool_t* p, racer_hstu_t* m, uint32_t layer, const 
   if (!p || !m || (B && !reqs) || layer >= m->cfg.L) return RACER_EINVAL;
   hipStream_t stream = static_cast<hipStream_t>(stream_v);
   StepCtx ctx;
-  int32_t rc = prepare_step(p, m, reqs, B, n_page_entries, stream, &ctx);
+  int32_t rc = prepare_step(p, m, reqs, B, n_page_entries, ts, stream, &ctx);
   if (rc) return rc;
   p->last_stream = stream;
   if (ctx.sl.N == 0) return RACER_OK;
   if (!page_tables || !q || !ts || !o) return RACER_EINVAL;
   if (m->cfg.elem == RACER_ELEM_BF16) {
     // the MFMA kernel takes q * log2(e); hstu_step's projection writes it that way, here it is a pre-pass
-    if ((rc = ensure_hstu_ws(p, ctx.sl.N, m->cfg.d, ctx.esize, stream))) return rc;
-    const uint64_t stride = ((static_cast<uint64_t>(p->hw_rows) * m->cfg.d * ctx.esize) + 255) & ~255ull;
+    if ((rc = ensure_hstu_ws(p, (static_cast<uint64_t>(ctx.sl.N) * m->cfg.d * ctx.esize + 255) & ~255ull, stream))) return rc;
+    const uint64_t stride = p->hw_slot;
     void* qs = p->hw_buf + 2 * stride;
     HIP_TRY(racer::launch_scale_q(q, qs, static_cast<uint64_t>(ctx.sl.N) * m->cfg.d, stream));
     q = qs;

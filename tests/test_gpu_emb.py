@@ -343,3 +343,32 @@ def test_random_sequences_of_lookups_refills_and_split_moves(seed):
             assert np.array_equal(out.cpu().numpy(), oout), step
         check_state(pool, orc, padded, "step %d op %d" % (step, op))
     pool.close()
+
+
+def test_split_change_whose_device_half_fails_leaves_everything_as_it_was():
+    # The failure is injected on the host, before any device work is queued (RACER_FAULT_INJECT names the call
+    # that is to fail once): the call reports the error, host bookkeeping is put back, and the pool goes on
+    # exactly like the oracle, which never saw the failed call.
+    import os
+    rng = synth.rng_for(0, 77)
+    rows, d = 3000, 64
+    table = synth.make_table(rng, rows, d, bf16=False)
+    pool, orc = make_pair(128, 16 * 2 * 1 * d * 4, d, False, 16, 32, table, 0.5)
+    for key, tokens in ((1, 300), (2, 500)):
+        assert B.kv_seq_reserve(pool.h, key, tokens)[0] == B.OK and orc.kv_reserve(key, tokens)[0] == oracle.OK
+    run_batches(pool, orc, table, [synth.zipf_ids(rng, rows, 0.9, 4000) for _ in range(3)], tag="before")
+    for frac in (0.25, 0.75):  # a shrink and a growth that drops the two cold sequences
+        before_stats, before_dump = pool.stats(), B.pool_dump(pool.h)
+        os.environ["RACER_FAULT_INJECT"] = "split"
+        rc, ach = B.pool_set_split(pool.h, frac)
+        os.environ.pop("RACER_FAULT_INJECT", None)
+        assert rc == B.EHIP and "injected" in B.last_error()
+        assert ach == 0.5 and pool.stats() == before_stats
+        after = B.pool_dump(pool.h)
+        assert np.array_equal(after["emb_pages"], before_dump["emb_pages"]) and np.array_equal(after["owner"], before_dump["owner"])
+        assert B.kv_seq_lookup(pool.h, 1)[0] == B.OK and B.kv_seq_lookup(pool.h, 2)[0] == B.OK
+        run_batches(pool, orc, table, [synth.zipf_ids(rng, rows, 0.9, 4000)], tag="after the failed move to %g" % frac)
+    for frac in (0.25, 0.75):  # the same moves for real
+        assert B.pool_set_split(pool.h, frac) == orc.set_split(frac)
+        run_batches(pool, orc, table, [synth.zipf_ids(rng, rows, 0.9, 4000)], tag="after the move to %g" % frac)
+    pool.close()

@@ -238,6 +238,29 @@ def test_bad_page_ids_are_skipped_and_counted(bf16, d):
     c.close()
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+def test_requests_with_decreasing_timestamps_follow_the_oracle(bf16):
+    # the interface asks for non-decreasing timestamps; a request that breaks this is still served like the oracle
+    # serves it (a negative gap falls into bucket 0), by the general time path, and counted
+    c = Case(15, 1, 128 if bf16 else 64, 2, 16, bf16, 512, 16, 512.0, 128)
+    prefix, new = [0, 100, 0], [200, 90, 140]
+    reqs, pts, ts, x = c.inputs(prefix, new)
+    ts = ts.copy()
+    (P, T, pto, tso, xo) = reqs[1]
+    seg = ts[tso:tso + P + T]
+    ts[tso:tso + P + T] = seg[np.random.default_rng(3).permutation(P + T)]   # request 1: any order
+    ts[reqs[2][3] + 70] = ts[reqs[2][3] + 69] - 5000                        # request 2: one step back
+    if P:  # request 1's cached prefix: one prefill step with the same timestamps
+        pre = [(0, P, pto, tso, 0)]
+        xp = c.rng.standard_normal((P, c.d)).astype(np.float32)
+        xp = synth.as_bf16_values(xp) if bf16 else xp
+        assert_close(c.run_gpu(pre, pts, ts, xp), c.run_oracle(pre, pts, ts, xp), bf16, "unordered timestamps, prefill")
+    got, ref = c.run_gpu(reqs, pts, ts, x), c.run_oracle(reqs, pts, ts, x)
+    assert_close(got, ref, bf16, "unordered timestamps")
+    assert c.pool.stats()["unordered_ts"] == 3  # request 1 twice (prefill and step), request 2 once
+    c.close()
+
+
 def test_shape_errors_are_reported():
     c = Case(7, 1, 64, 2, 16, False, 64, 8, 64.0, 64)
     reqs, pts, ts, x = c.inputs([0], [40])

@@ -44,6 +44,7 @@ def test_noalloc_lookup_equals_emb_lookup_on_two_calls_in_a_row(bag):
         tb, sb = pool.cache_dump()
         assert np.array_equal(ta, tb) and np.array_equal(sa, sb), n
         st_a, st_b = ref.stats(), pool.stats()
+        assert st_b.pop("ws_allocs") == 0 and st_a.pop("ws_allocs") > 0  # the library's own count of its allocations
         assert st_a == st_b, (st_a, st_b)
     assert ref.stats()["evicted"] > 0 and ref.stats()["hits"] > 0 and ref.stats()["invalid_ids"] > 0
     ref.close()
