@@ -528,29 +528,18 @@ def alpha_curve_bench(args, c, torch, Hn, B, synth):
 
         points = [measure(alpha, "grid") for alpha in grid]
         best = min(points, key=lambda q: q["total_ms"])
-        # Closed loop (the paper's Sec. IV-A controller picks a step from {0, +-0.05, +-0.1} each round; its trained
-        # policy is not available, so a hill climb on the measured step time stands in): from 0.8, each round tries
-        # the short step in the current direction, then the long one (which carries it over a flat stretch), then,
-        # once, the short step the other way; a move is kept if the time falls by more than 0.5 %; no move kept = stop.
-        alpha, cur, sign, path = 0.8, measure(0.8, "ctl"), -1.0, []
-        path.append({"alpha": alpha, "total_ms": float(cur["total_ms"]), "accepted": True})
-        for _ in range(14):
-            moved = False
-            for delta in (0.05 * sign, 0.1 * sign, -0.05 * sign):
-                nxt = round(min(0.8, max(0.2, alpha + delta)), 2)
-                if nxt == alpha or any(q["alpha"] == nxt and not q["accepted"] for q in path[-3:]):
-                    continue
-                cand = measure(nxt, "ctl")
-                ok = bool(cand["total_ms"] < cur["total_ms"] * 0.995)
-                path.append({"alpha": nxt, "total_ms": float(cand["total_ms"]), "accepted": ok})
-                if ok:
-                    alpha, cur, moved = nxt, cand, True
-                    sign = math.copysign(1.0, delta)
-                    break
-            if not moved:
-                break
-        if path[-1]["alpha"] != alpha:  # leave the pool at the split the controller settled on
-            B.pool_set_split(pool.h, alpha)
+        # Closed loop: the library's split controller (paper Sec. IV-A: action set {+-0.06, +-0.04, +-0.02, 0} of
+        # Eq. 3, alpha <- clip(alpha + step, 0.1, 0.9) of Eq. 6; its policy is a hill climb on the measured latency,
+        # a stand-in for the paper's trained policy), one decision per measured window, started at 0.8
+        ctl = B.AlphaController(slo_ms=30.0)
+        alpha, path = 0.8, []
+        for epoch in range(24):
+            cur = measure(alpha, "ctl")
+            step, nxt, burst = ctl.decide(alpha, float(cur["total_ms"]), kv_hit_rate=float(cur["kv_hit_rate"]),
+                                          emb_hit_rate=float(cur["emb_hit_rate"]), mean_seq_len=float(mean_len))
+            path.append({"alpha": alpha, "total_ms": float(cur["total_ms"]), "step": step, "burst": burst})
+            alpha = round(nxt, 2)
+        ctl.close()
         curves.append({"mean_history": int(mean_len), "best_alpha": best["alpha"], "best_total_ms": best["total_ms"],
                        "points": points, "controller_path": path, "controller_alpha": alpha})
         pool.close()

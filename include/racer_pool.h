@@ -267,6 +267,38 @@ int32_t hstu_attn_paged(racer_pool_t* pool, racer_hstu_t* model, uint32_t layer,
                         uint64_t n_page_entries, const void* q, const int64_t* ts, void* o,
                         void* stream);
 
+/* ---- split controller (paper Sec. IV-A "Adaptive EMB-KV Memory Allocation") -------------------------------
+ * Host only.  Once per decision epoch the caller hands over the state vector of Table I (what it measured
+ * over the last window: rates in [0, 1], lengths in tokens, latency in ms, alpha = the fraction that was in
+ * force) and receives a step out of the action set of Eq. 3, {+-0.06, +-0.04, +-0.02, 0}, and the next
+ * fraction clip(alpha + step, 0.1, 0.9) (Eq. 4, Eq. 6), which it applies with pool_set_split.  The paper's
+ * policy networks (PPO base policy, Online Adapter) were trained on traces that are not published; the
+ * policy here is a stand-in, a hill climb on the measured P99 latency (the objective of Eq. 1): it keeps
+ * its direction and step while the latency falls, turns back with the next smaller step when it rises,
+ * shrinks the step when nothing changes, holds when the step has reached 0, and probes again with 0.02 after
+ * six epochs or when the latency drifts up by more than 10 %.  The Recovery Controller is the paper's rule:
+ * an epoch whose latency exceeds the mean of the last ten epochs by more than three standard deviations
+ * (floored at 5 % of that mean, so that the controller's own probes on a quiet system are no bursts) is a
+ * burst (*burst = 1); the step is then -0.06 (memory towards the KV cache) if the hot-user ratio exceeds
+ * 0.2, else 0, and the climb starts over afterwards.  slo_ms = tau_SLO.  No parity claim against the
+ * paper's controller is possible.
+ * alpha_ctl_reward: the reward of Eq. 5, slo_satisfaction - max(0, p99 - slo) / slo. */
+typedef struct racer_alpha_ctl racer_alpha_ctl_t;
+typedef struct {
+  double hot_user_ratio;  /* h_t: share of the window's requests that came from hot users */
+  double kv_hit_rate;     /* k_t */
+  double emb_hit_rate;    /* e_t */
+  double mean_seq_len;    /* L_t */
+  double slo_violation;   /* v_t */
+  double alpha;           /* alpha_t */
+  double p99_latency_ms;  /* l_t */
+} racer_alpha_state;
+int32_t alpha_ctl_create(double slo_ms, racer_alpha_ctl_t** out);
+int32_t alpha_ctl_destroy(racer_alpha_ctl_t* ctl);
+int32_t alpha_ctl_decide(racer_alpha_ctl_t* ctl, const racer_alpha_state* s, double* step /* may be NULL */,
+                         double* alpha_next, int32_t* burst /* may be NULL */);
+double alpha_ctl_reward(double slo_satisfaction, double p99_latency_ms, double slo_ms);
+
 /* ---- per-kernel-class timing for benchmarks: when enabled, every launch (the miss path as
  *      one group) is bracketed by HIP events on the caller's stream.  racer_prof_read waits
  *      for the pool's last stream, adds up the intervals recorded since the previous read and

@@ -21,6 +21,7 @@ EXPORTS = [
     "pool_num_sets", "pool_slot_of", "kv_seq_reserve", "kv_seq_lookup", "kv_seq_pin", "kv_seq_unpin",
     "kv_seq_release", "emb_lookup", "emb_lookup_noalloc", "emb_refill", "pool_add_table", "emb_lookup_tables", "hstu_model_create", "hstu_model_destroy", "hstu_step",
     "hstu_attn_paged", "racer_last_error", "racer_prof_enable", "racer_prof_read",
+    "alpha_ctl_create", "alpha_ctl_destroy", "alpha_ctl_decide", "alpha_ctl_reward",
 ]
 PROF_KINDS = ("emb_gather", "emb_miss", "layernorm", "gemm_front", "attention", "gemm_back", "attn_reduce")
 
@@ -48,6 +49,11 @@ class PoolStats(C.Structure):
 class Reserve(C.Structure):
     _fields_ = [("max_lookups", C.c_uint64), ("max_requests", C.c_uint32), ("max_new_tokens", C.c_uint64),
                 ("max_seq_tokens", C.c_uint32)]
+
+
+class AlphaState(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("hot_user_ratio", "kv_hit_rate", "emb_hit_rate", "mean_seq_len",
+                                          "slo_violation", "alpha", "p99_latency_ms")]
 
 
 class HstuCfg(C.Structure):
@@ -93,6 +99,11 @@ def load():
     for f in (L.kv_seq_pin, L.kv_seq_unpin, L.kv_seq_release):
         f.argtypes = [vp, u64]
     L.pool_reserve.argtypes = [vp, vp, C.POINTER(Reserve), vp]
+    L.alpha_ctl_create.argtypes = [C.c_double, C.POINTER(vp)]
+    L.alpha_ctl_destroy.argtypes = [vp]
+    L.alpha_ctl_decide.argtypes = [vp, C.POINTER(AlphaState), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+    L.alpha_ctl_reward.argtypes = [C.c_double, C.c_double, C.c_double]
+    L.alpha_ctl_reward.restype = C.c_double
     L.emb_lookup.argtypes = [vp, vp, u64, u32, vp, vp, vp]
     L.emb_lookup_noalloc.argtypes = [vp, vp, u64, u32, vp, vp, vp]
     L.emb_refill.argtypes = [vp, vp, u64, vp]
@@ -106,7 +117,7 @@ def load():
     L.racer_prof_read.argtypes = [vp, C.POINTER(Prof)]
     L.racer_last_error.restype = C.c_char_p
     for name in EXPORTS:
-        if name not in ("pool_num_sets", "pool_slot_of", "racer_last_error"):
+        if name not in ("pool_num_sets", "pool_slot_of", "racer_last_error", "alpha_ctl_reward"):
             getattr(L, name).restype = i32
     _lib = L
     return L
@@ -169,6 +180,40 @@ def pool_reserve(pool, model, max_lookups=0, max_requests=0, max_new_tokens=0, m
     """Size the library's work spaces ahead of time (model: handle or None)."""
     r = Reserve(max_lookups, max_requests, max_new_tokens, max_seq_tokens)
     return load().pool_reserve(pool, model, C.byref(r), _stream_ptr(stream))
+
+
+class AlphaController:
+    """The split controller: decide(...) -> (step, next fraction, burst flag)."""
+
+    def __init__(self, slo_ms):
+        self.h = C.c_void_p()
+        rc = load().alpha_ctl_create(float(slo_ms), C.byref(self.h))
+        if rc != OK:
+            raise ValueError("alpha_ctl_create failed: %d" % rc)
+
+    def decide(self, alpha, p99_latency_ms, hot_user_ratio=0.0, kv_hit_rate=0.0, emb_hit_rate=0.0, mean_seq_len=0.0,
+               slo_violation=0.0):
+        s = AlphaState(hot_user_ratio, kv_hit_rate, emb_hit_rate, mean_seq_len, slo_violation, alpha, p99_latency_ms)
+        step, nxt, burst = C.c_double(0.0), C.c_double(0.0), C.c_int32(0)
+        rc = load().alpha_ctl_decide(self.h, C.byref(s), C.byref(step), C.byref(nxt), C.byref(burst))
+        if rc != OK:
+            raise ValueError("alpha_ctl_decide failed: %d" % rc)
+        return step.value, nxt.value, bool(burst.value)
+
+    def close(self):
+        if self.h:
+            load().alpha_ctl_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def alpha_reward(slo_satisfaction, p99_latency_ms, slo_ms):
+    return load().alpha_ctl_reward(float(slo_satisfaction), float(p99_latency_ms), float(slo_ms))
 
 
 def pool_stats(pool):

@@ -15,6 +15,7 @@
 #include "../../include/racer_pool.h"  // also fixes RACER_NOALLOC_MAX_*
 #include "kernels.h"
 #include "pool_host.h"
+#include "alpha_ctl.h"
 
 namespace {
 
@@ -1213,6 +1214,37 @@ int32_t hstu_attn_paged(racer_pool_t* p, racer_hstu_t* m, uint32_t layer, const 
     HIP_TRY(racer::launch_attention_reduce(ctx.hd, ctx.sl, o, stream));
   }
   return RACER_OK;
+}
+
+// ---- split controller (host only) --------------------------------------------------------------------------
+
+int32_t alpha_ctl_create(double slo_ms, racer_alpha_ctl_t** out) {
+  if (!out) return RACER_EINVAL;
+  *out = nullptr;
+  if (!(slo_ms > 0.0)) return RACER_EINVAL;
+  racer::AlphaController* c = new (std::nothrow) racer::AlphaController(slo_ms);
+  if (!c) return RACER_ENOMEM;
+  *out = reinterpret_cast<racer_alpha_ctl_t*>(c);
+  return RACER_OK;
+}
+
+int32_t alpha_ctl_destroy(racer_alpha_ctl_t* ctl) {
+  if (!ctl) return RACER_EINVAL;
+  delete reinterpret_cast<racer::AlphaController*>(ctl);
+  return RACER_OK;
+}
+
+int32_t alpha_ctl_decide(racer_alpha_ctl_t* ctl, const racer_alpha_state* s, double* step, double* alpha_next, int32_t* burst) {
+  if (!ctl || !s || !alpha_next) return RACER_EINVAL;
+  if (!(s->alpha >= 0.0 && s->alpha <= 1.0) || !(s->p99_latency_ms >= 0.0)) return RACER_EINVAL;
+  const racer::AlphaState st{s->hot_user_ratio, s->kv_hit_rate, s->emb_hit_rate, s->mean_seq_len, s->slo_violation,
+                             s->alpha, s->p99_latency_ms};
+  *alpha_next = reinterpret_cast<racer::AlphaController*>(ctl)->decide(st, step, burst);
+  return RACER_OK;
+}
+
+double alpha_ctl_reward(double slo_satisfaction, double p99_latency_ms, double slo_ms) {
+  return racer::alpha_reward(slo_satisfaction, p99_latency_ms, slo_ms);
 }
 
 int32_t racer_prof_enable(racer_pool_t* p, int32_t on) {

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "racer_pool.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"^\s*(?:const\s+)?(?:int32_t|uint64_t|int64_t|char\s*\*)\s*\*?\s*([a-z_0-9]+)\s*\(", text, flags=re.M)
+    names = re.findall(r"^\s*(?:const\s+)?(?:int32_t|uint64_t|int64_t|double|char\s*\*)\s*\*?\s*([a-z_0-9]+)\s*\(", text, flags=re.M)
     return sorted(set(names))
 
 
