@@ -93,15 +93,21 @@ CONFIGS = {
 
 
 def measured_traffic(kernel, workload):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    """(HBM bytes per launch of `kernel`, where the figure comes from) out of the committed rocprofv3 counter summary,
+    or (None, None).  The figure is not measured by this run: it is the summary's, and the source names the file and
+    the commit the summary says it was taken at."""
+    rel = os.path.join("profiles", "hbm_traffic_%s.txt" % workload)
+    value, commit = None, "unknown commit"
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             if line.startswith("traffic.%s.%s=" % (kernel, workload)):
-                return float(line.split("=")[1])
+                value = float(line.split("=")[1])
+            if line.startswith("measured_at_commit="):
+                commit = line.split("=")[1].strip()
     except OSError:
         pass
-    return None
+    return (value, "%s @ %s (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not re-measured by this run)" % (rel, commit)) \
+        if value is not None else (None, None)
 
 
 def build_workload(c, torch, Hn, B, synth):
@@ -147,9 +153,11 @@ def build_workload(c, torch, Hn, B, synth):
     return wl
 
 
-def emb_only_bench(args, c, torch, Hn, B, synth):
-    """Lookups only (pooled): whole emb_lookup calls per second and the probe+gather kernel against HBM."""
+def emb_only_measure(args, c, torch, Hn, B, synth, steps=None):
+    """Lookups only (pooled): whole emb_lookup calls per second and the probe+gather kernel against HBM.
+    Returns the result line as a dict."""
     dev = Hn.DEV
+    steps = steps or args.steps
     d, pt, L, bag = c["d"], c["pt"], c["L"], c["bag"]
     table = torch.empty((c["rows"], d), dtype=torch.int16, pin_memory=True)
     synth.fill_table_bf16_torch(table, synth.SEED_BASE + c["index"], dev)
@@ -159,7 +167,7 @@ def emb_only_bench(args, c, torch, Hn, B, synth):
     pool = Hn.Pool(n_pages, page_size, d * 2, B.ELEM_BF16, pt, 32, table.view(torch.bfloat16), c["alpha"])
     rng = synth.rng_for(c["index"], 11)
     tokens = c["batch"] * c["mean_len"]
-    n_sets = c["warm_batches"] + args.warmup + args.steps
+    n_sets = c["warm_batches"] + args.warmup + steps
     out = torch.empty((tokens, d), dtype=torch.bfloat16, device=dev)
     ids_dev = []
     for k in range(n_sets):
@@ -180,7 +188,7 @@ def emb_only_bench(args, c, torch, Hn, B, synth):
     B.racer_prof_enable(pool.h, 1)
     B.racer_prof_read(pool.h)
     t0 = time.perf_counter()
-    for k in range(args.steps):
+    for k in range(steps):
         rc = B.emb_lookup(pool.h, ids_dev[c["warm_batches"] + args.warmup + k], out, bag, None)
         assert rc == B.OK, (rc, B.last_error())
     torch.cuda.synchronize()
@@ -193,23 +201,28 @@ def emb_only_bench(args, c, torch, Hn, B, synth):
     R = d * 2
     ways = st1["pages_emb"] / (n_pages / 32)
     # id + tag line + stamp per lookup, the row read of every hit, the pooled rows written
-    gather_bytes = (lookups * (8 + 4 * ways + 4) + hits * R) / args.steps + tokens * R
+    gather_bytes = (lookups * (8 + 4 * ways + 4) + hits * R) / steps + tokens * R
     gather_ms = prof["emb_gather"][0] / max(prof["emb_gather"][1], 1)
     gbs = gather_bytes / (gather_ms * 1e-3) / 1e9 if gather_ms > 0 else 0.0
-    ms = dt * 1e3 / args.steps
+    ms = dt * 1e3 / steps
     result = {
         "metric": "emb_lookup_tokens_per_s", "value": tokens / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "steps": steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": c["desc"], "tokens_per_step": tokens, "lookups_per_step": tokens * bag,
-                   "hit_rate": hits / max(lookups, 1), "unique_misses_per_step": (st1["unique_misses"] - st0["unique_misses"]) / args.steps},
+                   "hit_rate": hits / max(lookups, 1), "unique_misses_per_step": (st1["unique_misses"] - st0["unique_misses"]) / steps},
         "roofline": {"kernel": "emb_probe_gather", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": gbs / PEAK_HBM_GBS, "traffic": None, "bytes_per_launch": gather_bytes, "ms_per_launch": gather_ms},
-        "kernels": {k: {"ms_per_launch": (v[0] / v[1] if v[1] else 0.0), "launches_per_step": v[1] / args.steps}
+        "kernels": {k: {"ms_per_launch": (v[0] / v[1] if v[1] else 0.0), "launches_per_step": v[1] / steps}
                     for k, v in prof.items() if v[1]},
     }
-    print(json.dumps(result))
     pool.close()
+    del pool, table, out, ids_dev
+    return result
+
+
+def emb_only_bench(args, c, torch, Hn, B, synth):
+    print(json.dumps(emb_only_measure(args, c, torch, Hn, B, synth)))
 
 
 def attn_only_bench(args, c, torch, Hn, B, synth):
@@ -858,6 +871,8 @@ def main():
     ap.add_argument("--config", default="mid", choices=sorted(CONFIGS))
     ap.add_argument("--cpu-tokens", type=int, default=None, help="token budget of the oracle sample")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-embheavy", action="store_true",
+                    help="leave out the EMB-heavy lookups-only pass (the gather against HBM proper) that the default run appends")
     ap.add_argument("--one-pipeline", action="store_true",
                     help="run the throughput pass as one pipeline as well (per-kernel events on): every kernel launch "
                          "then covers the whole batch, which is what a per-kernel profile of the run needs")
@@ -954,6 +969,7 @@ def main():
     gather_gbs = gather_bytes / (gather_ms * 1e-3) / 1e9 if gather_ms > 0 else 0.0
     kernels = {k: {"ms_per_launch": (v[0] / v[1] if v[1] else 0.0), "launches_per_step": v[1] / args.steps}
                for k, v in prof.items()}
+    traffic, traffic_source = measured_traffic("attention_bf16_mfma", args.config) if c["bf16"] else (None, None)
     result = {
         "metric": "hstu_step_tokens_per_s", "value": N / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -971,7 +987,7 @@ def main():
         "roofline": {"kernel": "attention_bf16_mfma" if c["bf16"] else "attention_f32", "bound": "mfma",
                      "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": attn_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": measured_traffic("attention_bf16_mfma", args.config) if c["bf16"] else None,
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "flop_per_launch": attn_flop, "ms_per_launch": attn_ms},
         "kernels": kernels,
     }
@@ -992,9 +1008,24 @@ def main():
                             "row_norm": result["parity_max_rel_err"],
                             "elementwise_floor_1e-2": float(parity.rel_error_elem(got[rows], ref).max()),
                             "tolerance_row_norm": parity.TOL_ROW[bool(c["bf16"])]}
-    print(json.dumps(result))
     wl["model"].close()
     pool.close()
+    if args.config == "mid" and not args.no_embheavy:
+        # The Mid batch's gather is served largely from the caches (the figure above is an effective rate).  The gather
+        # against HBM proper is the EMB-heavy configuration (2.1 M pooled lookups spread over a 40 GiB hot cache),
+        # lookups only, timed here too so that the line carries it.
+        del wl, pool
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+        eh = emb_only_measure(args, CONFIGS["embheavy"], torch, Hn, B, synth, steps=min(args.steps, 20))
+        result["emb_gather_hbm"] = {"workload": CONFIGS["embheavy"]["desc"], "GBps": eh["roofline"]["achieved"],
+                                    "frac_of_hbm_peak": eh["roofline"]["frac"],
+                                    "bytes_per_launch": eh["roofline"]["bytes_per_launch"],
+                                    "ms_per_launch": eh["roofline"]["ms_per_launch"],
+                                    "hit_rate": eh["config"]["hit_rate"], "lookups_per_launch": eh["config"]["lookups_per_step"],
+                                    "ms_per_emb_lookup_call": eh["ms_per_step"]}
+    print(json.dumps(result))
 
 
 if __name__ == "__main__":

@@ -3,8 +3,14 @@
 //   Xn = LayerNorm(X);  [U|V|Q|K] = SiLU(Xn W1 + b1);  K,V of the new tokens -> KV pages
 //   O_i = (1/n) sum_{j<=p_i} SiLU(q_i.k_j + pos[min(p_i-j, n_pos-1)] + time[bucket(ts_p-ts_j)]) v_j
 //   Y = X + (LayerNorm(O) * U) W2 + b2
-// bf16 models run on MFMA (v_mfma_f32_32x32x16_bf16) with fp32 accumulation; the small
-// fp32 configuration uses plain FMA kernels.
+// bf16 models run on MFMA with fp32 accumulation; the small fp32 configuration uses plain FMA kernels.
+// What a bf16 model stores where a caller can see it (inputs, weights, K and V in the pages, outputs) is bf16.
+// The library's own intermediate matrices (the normalised activations, U, the attention output O, the gated
+// activations) and its transposed copies of the weights are IEEE half precision: eleven significant bits
+// instead of eight at the same size and the same MFMA rate (v_mfma_f32_32x32x16_f16), which halves the
+// distance to the fp64 oracle; a bf16 weight converts exactly.  Values of these matrices must stay below
+// 65504 in magnitude, which LayerNorm and the 1/n scaling ensure for any sane model.  The two attention
+// products take bf16 operands (Q, and K, V as the pages hold them).
 //
 // KV page layout (one page = page_tokens tokens of every layer):
 //   [layer][K|V][head] blocks of page_tokens*d_h elements;
@@ -19,6 +25,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 struct bf16_t { uint16_t bits; };
+struct half_t { uint16_t bits; };  // IEEE binary16 (the library's own intermediates)
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
 __device__ __forceinline__ uint16_t f2bf(float f) {
@@ -26,6 +35,7 @@ __device__ __forceinline__ uint16_t f2bf(float f) {
   if ((u & 0x7FFFFFFFu) > 0x7F800000u) return static_cast<uint16_t>((u >> 16) | 0x40);
   return static_cast<uint16_t>((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
 }
+__device__ __forceinline__ uint16_t f2h(float f) { return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f)); }  // nearest even
 __device__ __forceinline__ float load_elem(const float* p, uint64_t i) { return p[i]; }
 __device__ __forceinline__ float load_elem(const bf16_t* p, uint64_t i) { return bf2f(p[i].bits); }
 __device__ __forceinline__ void store_elem(float* p, uint64_t i, float v) { p[i] = v; }
@@ -81,19 +91,28 @@ __device__ __forceinline__ void load8(const bf16_t* p, float v[8]) {
     v[2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
   }
 }
+__device__ __forceinline__ void load8(const half_t* p, float v[8]) {
+  const uint4 a = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const f16x2 h = __builtin_bit_cast(f16x2, w[k]);
+    v[2 * k] = static_cast<float>(h[0]);
+    v[2 * k + 1] = static_cast<float>(h[1]);
+  }
+}
+__device__ __forceinline__ uint32_t pack2_f16(float lo, float hi) {
+  typedef float v2f __attribute__((ext_vector_type(2)));
+  const v2f v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
+__device__ __forceinline__ void store8(half_t* p, const float v[8]) {
+  *reinterpret_cast<uint4*>(p) = make_uint4(pack2_f16(v[0], v[1]), pack2_f16(v[2], v[3]), pack2_f16(v[4], v[5]), pack2_f16(v[6], v[7]));
+}
 __device__ __forceinline__ void store8(float* p, const float v[8]) {
   *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
   *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
 }
-__device__ __forceinline__ void store8(bf16_t* p, const float v[8]) {
-  uint4 a;
-  a.x = f2bf(v[0]) | (static_cast<uint32_t>(f2bf(v[1])) << 16);
-  a.y = f2bf(v[2]) | (static_cast<uint32_t>(f2bf(v[3])) << 16);
-  a.z = f2bf(v[4]) | (static_cast<uint32_t>(f2bf(v[5])) << 16);
-  a.w = f2bf(v[6]) | (static_cast<uint32_t>(f2bf(v[7])) << 16);
-  *reinterpret_cast<uint4*>(p) = a;
-}
-
 template <int LPR>
 __device__ __forceinline__ float group_sum(float v) {  // sum over the LPR lanes that share a row
 #pragma unroll
@@ -101,10 +120,10 @@ __device__ __forceinline__ float group_sum(float v) {  // sum over the LPR lanes
   return v;
 }
 
-template <typename T, int LPR, int KC>
-__global__ __launch_bounds__(256) void layernorm_rows(const T* __restrict__ x, const float* __restrict__ g,
-                                                      const float* __restrict__ b, const T* __restrict__ gate,
-                                                      T* __restrict__ y, uint32_t N, uint32_t d, float eps) {
+template <typename TX, typename TY, int LPR, int KC>  // TX: input rows; TY: gate rows and output rows
+__global__ __launch_bounds__(256) void layernorm_rows(const TX* __restrict__ x, const float* __restrict__ g,
+                                                      const float* __restrict__ b, const TY* __restrict__ gate,
+                                                      TY* __restrict__ y, uint32_t N, uint32_t d, float eps) {
   const uint32_t sub = threadIdx.x % LPR;
   const uint32_t row = blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
   const bool row_ok = row < N;  // lanes of a missing row still take part in the shuffles
@@ -204,9 +223,10 @@ struct BackEpilogue {  // y = x + acc + b2
 };
 
 // ---------------------------------------------------------------------------------------
-// bf16 GEMM on MFMA: C[M][Nout] = A[M][K] * Bt[Nout][K]^T, block tile 128 x 64, four
+// Half-precision GEMM on MFMA (both operands are the library's own: a normalised activation matrix and a
+// transposed weight copy): C[M][Nout] = A[M][K] * Bt[Nout][K]^T, block tile 128 x 64, four
 // wavefronts of 32 rows x 64 columns each, K staged through LDS 64 at a time.
-// Operand layout of v_mfma_f32_32x32x16_bf16: lane (g = lane/32, i = lane%32) supplies row
+// Operand layout of v_mfma_f32_32x32x16_f16 / _bf16: lane (g = lane/32, i = lane%32) supplies row
 // (A) or column (B) i with eight consecutive k of its half g; the result lane holds column
 // i and rows 8*(r/4) + 4*g + r%4 for r = 0..15.
 // ---------------------------------------------------------------------------------------
@@ -242,11 +262,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma(const uint16_t* __restrict
     __syncthreads();
 #pragma unroll
     for (int st = 0; st < 4; ++st) {
-      const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&As[32 * wave + li][16 * st + 8 * g]));
+      const f16x8 a = __builtin_bit_cast(f16x8, *reinterpret_cast<const uint4*>(&As[32 * wave + li][16 * st + 8 * g]));
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb) {
-        const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Bs[32 * cb + li][16 * st + 8 * g]));
-        acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[cb], 0, 0, 0);
+        const f16x8 b = __builtin_bit_cast(f16x8, *reinterpret_cast<const uint4*>(&Bs[32 * cb + li][16 * st + 8 * g]));
+        acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[cb], 0, 0, 0);
       }
     }
     __syncthreads();
@@ -300,11 +320,11 @@ __global__ __launch_bounds__(256) void gemm_front_bf16(HstuDims hd, uint32_t lay
     __syncthreads();
 #pragma unroll
     for (int st = 0; st < 4; ++st) {
-      const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&As[32 * wave + li][16 * st + 8 * g]));
+      const f16x8 a = __builtin_bit_cast(f16x8, *reinterpret_cast<const uint4*>(&As[32 * wave + li][16 * st + 8 * g]));
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb) {
-        const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Bs[32 * cb + li][16 * st + 8 * g]));
-        acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[cb], 0, 0, 0);
+        const f16x8 b = __builtin_bit_cast(f16x8, *reinterpret_cast<const uint4*>(&Bs[32 * cb + li][16 * st + 8 * g]));
+        acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[cb], 0, 0, 0);
       }
     }
     __syncthreads();
@@ -318,7 +338,8 @@ __global__ __launch_bounds__(256) void gemm_front_bf16(HstuDims hd, uint32_t lay
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const uint32_t row = 32 * wave + 8 * (r / 4) + 4 * g + (r % 4);
-      As[row][32 * cb + li] = f2bf(silu(acc[cb][r] + bias) * qscale);
+      const float z = silu(acc[cb][r] + bias) * qscale;
+      As[row][32 * cb + li] = which == 0 ? f2h(z) : f2bf(z);  // U is the library's own (half precision); Q, K, V are bf16
     }
   }
   __syncthreads();
@@ -391,6 +412,7 @@ __global__ __launch_bounds__(256) void gemm_front_bf16(HstuDims hd, uint32_t lay
 //   FRONT: [U|V|Q|K] = SiLU(LN1(X) W1 + b1), U and Q*log2(e) to row-major buffers, K and V into
 //          the pages;
 //   BACK:  Y = X + (LN2(O) * U) W2 + b2.
+// (X, Q, K, V, Y are bf16; O, U, the normalised operand and the weight copies are half precision.)
 // A wavefront owns 32 token rows.  Their activations are loaded once (whole-line loads, dealt
 // out to the lanes through LDS), normalised in registers (a row is split over the two lanes
 // (g = 0, 1) that share the token: two cross-lane sums) and kept as the token-side MFMA operand
@@ -429,13 +451,28 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
   const v2f v = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, v2bf));
 }
-__device__ __forceinline__ void unpack8(const uint4& a, float v[8]) {
+__device__ __forceinline__ void unpack8(const uint4& a, float v[8]) {  // eight bf16
   const uint32_t w[4] = {a.x, a.y, a.z, a.w};
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     v[2 * k] = __uint_as_float(w[k] << 16);
     v[2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
   }
+}
+__device__ __forceinline__ void unpack8h(const uint4& a, float v[8]) {  // eight half-precision values
+  const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const f16x2 h = __builtin_bit_cast(f16x2, w[k]);
+    v[2 * k] = static_cast<float>(h[0]);
+    v[2 * k + 1] = static_cast<float>(h[1]);
+  }
+}
+// the rows a layer half normalises: the bf16 residual stream (front) or the half-precision attention output (back)
+template <bool FRONT>
+__device__ __forceinline__ void unpack_in(const uint4& a, float v[8]) {
+  if (FRONT) unpack8(a, v);
+  else unpack8h(a, v);
 }
 
 // Tells the compiler nothing about the value it returns: the unpacked fp32 copy of a row that an
@@ -555,7 +592,7 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
 #pragma unroll
     for (int st = 0; st < kSt; ++st) {
       float v[8];
-      unpack8(xr[st], v);
+      unpack_in<FRONT>(xr[st], v);
 #pragma unroll
       for (int e = 0; e < 8; ++e) s += v[e];
     }
@@ -567,7 +604,7 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
 #pragma unroll
     for (int st = 0; st < kSt; ++st) {
       float v[8];
-      unpack8(xr[st], v);
+      unpack_in<FRONT>(xr[st], v);
 #pragma unroll
       for (int e = 0; e < 8; ++e) qq += (v[e] - mean) * (v[e] - mean);
     }
@@ -579,18 +616,18 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
 #pragma unroll
     for (int st = 0; st < kSt; ++st) {
       float v[8], gg[8], bb[8];
-      unpack8(xr[st], v);
+      unpack_in<FRONT>(xr[st], v);
       load8(&lnp[0][16 * st + 8 * g], gg);
       load8(&lnp[1][16 * st + 8 * g], bb);
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = (v[e] - mean) * rstd * gg[e] + bb[e];
       if (!FRONT) {
         float uv[8];
-        unpack8(gr[st], uv);
+        unpack8h(gr[st], uv);
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] *= uv[e];
       }
-      xr[st] = make_uint4(pack2_bf16(v[0], v[1]), pack2_bf16(v[2], v[3]), pack2_bf16(v[4], v[5]), pack2_bf16(v[6], v[7]));
+      xr[st] = make_uint4(pack2_f16(v[0], v[1]), pack2_f16(v[2], v[3]), pack2_f16(v[4], v[5]), pack2_f16(v[6], v[7]));
       // the result is pinned down here and memory operations may not pass: the LDS reads of later
       // steps stay behind this step's arithmetic instead of piling up in registers
       forget(xr[st]);
@@ -669,8 +706,8 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
     }
 #pragma unroll
     for (int st = 0; st < kSt; ++st) {
-      const bf16x8 wf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(wb + swz[st & 3] + 64 * (st >> 2)));
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, __builtin_bit_cast(bf16x8, xr[st]), acc, 0, 0, 0);
+      const f16x8 wf = __builtin_bit_cast(f16x8, *reinterpret_cast<const uint4*>(wb + swz[st & 3] + 64 * (st >> 2)));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf, __builtin_bit_cast(f16x8, xr[st]), acc, 0, 0, 0);
     }
     if (!wave_has_rows) return;
     if (FRONT) {
@@ -693,7 +730,9 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4)
         *reinterpret_cast<uint2*>(ot + li * kOutStride + 8 * r4 + 4 * g) =
-            make_uint2(pack2_bf16(z[4 * r4] * sc, z[4 * r4 + 1] * sc), pack2_bf16(z[4 * r4 + 2] * sc, z[4 * r4 + 3] * sc));
+            which == 0  // U is the library's own (half precision); Q and K are bf16
+                ? make_uint2(pack2_f16(z[4 * r4], z[4 * r4 + 1]), pack2_f16(z[4 * r4 + 2], z[4 * r4 + 3]))
+                : make_uint2(pack2_bf16(z[4 * r4] * sc, z[4 * r4 + 1] * sc), pack2_bf16(z[4 * r4 + 2] * sc, z[4 * r4 + 3] * sc));
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2) {
         const uint4 v = *reinterpret_cast<const uint4*>(ot + ((lane >> 2) + 16 * h2) * kOutStride + 8 * (lane & 3));
@@ -881,7 +920,9 @@ __device__ __forceinline__ float silu_log2(float y) {
 }
 
 // NQB = 32-query groups per wavefront (1: 128 queries per block, three resident blocks per CU).
-template <int NQB>
+// OHALF: the output goes out in half precision (the step's own matrix between the attention and the second
+// LayerNorm) instead of bf16 (what a caller of the attention alone gets).
+template <int NQB, bool OHALF>
 __global__ __launch_bounds__(256, NQB == 1 ? 3 : 2) void attention_bf16_mfma(HstuDims hd, uint32_t layer, const uint16_t* __restrict__ q,
                                                               const float* __restrict__ pos,
                                                               const float* __restrict__ time, KvView kv,
@@ -1282,8 +1323,13 @@ __global__ __launch_bounds__(256, NQB == 1 ? 3 : 2) void attention_bf16_mfma(Hst
 #pragma unroll
         for (int e4 = 0; e4 < 4; ++e4) {
           uint2 w;
-          w.x = pack_bf16x2(oacc[qb][db][4 * e4] * sc, oacc[qb][db][4 * e4 + 1] * sc);
-          w.y = pack_bf16x2(oacc[qb][db][4 * e4 + 2] * sc, oacc[qb][db][4 * e4 + 3] * sc);
+          if (OHALF) {
+            w.x = pack2_f16(oacc[qb][db][4 * e4] * sc, oacc[qb][db][4 * e4 + 1] * sc);
+            w.y = pack2_f16(oacc[qb][db][4 * e4 + 2] * sc, oacc[qb][db][4 * e4 + 3] * sc);
+          } else {
+            w.x = pack_bf16x2(oacc[qb][db][4 * e4] * sc, oacc[qb][db][4 * e4 + 1] * sc);
+            w.y = pack_bf16x2(oacc[qb][db][4 * e4 + 2] * sc, oacc[qb][db][4 * e4 + 3] * sc);
+          }
           *reinterpret_cast<uint2*>(orow + 32 * db + 8 * e4 + 4 * g) = w;
         }
     }
@@ -1293,7 +1339,8 @@ __global__ __launch_bounds__(256, NQB == 1 ? 3 : 2) void attention_bf16_mfma(Hst
 // Sum the fp32 partials of a split query tile in chunk order and write the bf16 output.
 __global__ __launch_bounds__(256) void attention_reduce(HstuDims hd, uint32_t q_block, const ReqDev* __restrict__ reqs,
                                                         const AttnGroup* __restrict__ groups,
-                                                        const float* __restrict__ partials, uint16_t* __restrict__ o) {
+                                                        const float* __restrict__ partials, uint16_t* __restrict__ o,
+                                                        uint32_t o_half) {
   // blockIdx.x = (group, head); blockIdx.y = which 16 of the tile's query rows: a thread owns one 16-byte piece of
   // one row, so that the chunks' loads of a whole tile are in flight at once
   const AttnGroup gr = groups[blockIdx.x / hd.H];
@@ -1322,8 +1369,13 @@ __global__ __launch_bounds__(256) void attention_reduce(HstuDims hd, uint32_t q_
     acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
   }
   uint2 w;
-  w.x = pack_bf16x2(acc.x, acc.y);
-  w.y = pack_bf16x2(acc.z, acc.w);
+  if (o_half) {
+    w.x = pack2_f16(acc.x, acc.y);
+    w.y = pack2_f16(acc.z, acc.w);
+  } else {
+    w.x = pack_bf16x2(acc.x, acc.y);
+    w.y = pack_bf16x2(acc.z, acc.w);
+  }
   *reinterpret_cast<uint2*>(o + static_cast<uint64_t>(rq.x_off + qi) * hd.d + h * 64 + 4 * c4) = w;
 }
 
@@ -1369,18 +1421,29 @@ __global__ void transpose_kernel(const T* __restrict__ w, T* __restrict__ wt, ui
     if (bx + yy < cols && by + threadIdx.x < rows) wt[static_cast<uint64_t>(bx + yy) * rows + by + threadIdx.x] = tile[threadIdx.x][yy];
 }
 
+// transposed copy of a bf16 weight matrix in half precision (exact unless a weight is below 2^-14 in magnitude)
+__global__ void transpose_bf16_to_f16(const uint16_t* __restrict__ w, uint16_t* __restrict__ wt, uint32_t rows, uint32_t cols) {
+  __shared__ uint16_t tile[32][33];
+  const uint32_t bx = blockIdx.x * 32, by = blockIdx.y * 32;
+  for (uint32_t yy = threadIdx.y; yy < 32; yy += 8)
+    if (by + yy < rows && bx + threadIdx.x < cols) tile[yy][threadIdx.x] = f2h(bf2f(w[static_cast<uint64_t>(by + yy) * cols + bx + threadIdx.x]));
+  __syncthreads();
+  for (uint32_t yy = threadIdx.y; yy < 32; yy += 8)
+    if (bx + yy < cols && by + threadIdx.x < rows) wt[static_cast<uint64_t>(bx + yy) * rows + by + threadIdx.x] = tile[threadIdx.x][yy];
+}
+
 }  // namespace
 
-template <typename T>
+template <typename TX, typename TY>
 static void layernorm_dispatch(const HstuDims& hd, const void* x, const float* g, const float* b, const void* gate,
                                void* y, uint32_t N, hipStream_t stream) {
-  const T* xs = static_cast<const T*>(x);
-  const T* gs = static_cast<const T*>(gate);
-  T* ys = static_cast<T*>(y);
+  const TX* xs = static_cast<const TX*>(x);
+  const TY* gs = static_cast<const TY*>(gate);
+  TY* ys = static_cast<TY*>(y);
   const uint32_t chunks = hd.d / 8;
   const dim3 block(256);
-#define RACER_LN(LPR, KC)                                                                                   \
-  hipLaunchKernelGGL((layernorm_rows<T, LPR, KC>), dim3((N + 256 / LPR - 1) / (256 / LPR)), block, 0, stream, \
+#define RACER_LN(LPR, KC)                                                                                        \
+  hipLaunchKernelGGL((layernorm_rows<TX, TY, LPR, KC>), dim3((N + 256 / LPR - 1) / (256 / LPR)), block, 0, stream, \
                      xs, g, b, gs, ys, N, hd.d, hd.eps)
   if (chunks <= 8) RACER_LN(8, 1);
   else if (chunks <= 16) RACER_LN(16, 1);
@@ -1390,11 +1453,14 @@ static void layernorm_dispatch(const HstuDims& hd, const void* x, const float* g
 #undef RACER_LN
 }
 
+// bf16 models: the first LayerNorm of a layer reads the bf16 residual stream, the second one the half-precision
+// attention output and gate; both write half precision (the next product's operand)
 hipError_t launch_layernorm(const HstuDims& hd, const void* x, const float* g, const float* b, const void* gate,
                             void* y, uint32_t N, hipStream_t stream) {
   if (N == 0) return hipSuccess;
-  if (hd.elem == 1) layernorm_dispatch<bf16_t>(hd, x, g, b, gate, y, N, stream);
-  else layernorm_dispatch<float>(hd, x, g, b, gate, y, N, stream);
+  if (hd.elem != 1) layernorm_dispatch<float, float>(hd, x, g, b, gate, y, N, stream);
+  else if (gate) layernorm_dispatch<half_t, half_t>(hd, x, g, b, gate, y, N, stream);
+  else layernorm_dispatch<bf16_t, half_t>(hd, x, g, b, gate, y, N, stream);
   return hipGetLastError();
 }
 
@@ -1488,13 +1554,18 @@ hipError_t launch_gemm_back(const HstuDims& hd, const void* g, const void* w2, c
 
 hipError_t launch_attention(const HstuDims& hd, uint32_t layer, const void* q, const float* pos, const float* time,
                             const KvView& kv, const StepLists& sl, const int32_t* page_tables, const int64_t* ts,
-                            void* o, hipStream_t stream) {
+                            void* o, bool o_half, hipStream_t stream) {
   if (sl.N == 0) return hipSuccess;
   if (hd.elem == 1) {
     if (sl.q_block != 128) return hipErrorInvalidValue;  // the work items are cut for 128-query blocks
-    hipLaunchKernelGGL(attention_bf16_mfma<1>, dim3(sl.n_work), dim3(256), 0, stream, hd, layer,
-                       static_cast<const uint16_t*>(q), pos, time, kv, sl.reqs, sl.items, sl.work, sl.partials, page_tables,
-                       reinterpret_cast<const long long*>(ts), static_cast<uint16_t*>(o));
+    if (o_half)
+      hipLaunchKernelGGL((attention_bf16_mfma<1, true>), dim3(sl.n_work), dim3(256), 0, stream, hd, layer,
+                         static_cast<const uint16_t*>(q), pos, time, kv, sl.reqs, sl.items, sl.work, sl.partials, page_tables,
+                         reinterpret_cast<const long long*>(ts), static_cast<uint16_t*>(o));
+    else
+      hipLaunchKernelGGL((attention_bf16_mfma<1, false>), dim3(sl.n_work), dim3(256), 0, stream, hd, layer,
+                         static_cast<const uint16_t*>(q), pos, time, kv, sl.reqs, sl.items, sl.work, sl.partials, page_tables,
+                         reinterpret_cast<const long long*>(ts), static_cast<uint16_t*>(o));
   } else {
     const uint32_t items = sl.N * hd.H;
     hipLaunchKernelGGL(attention_f32, dim3((items + 3) / 4), dim3(256), 0, stream, hd, layer,
@@ -1504,10 +1575,10 @@ hipError_t launch_attention(const HstuDims& hd, uint32_t layer, const void* q, c
   return hipGetLastError();
 }
 
-hipError_t launch_attention_reduce(const HstuDims& hd, const StepLists& sl, void* o, hipStream_t stream) {
+hipError_t launch_attention_reduce(const HstuDims& hd, const StepLists& sl, void* o, bool o_half, hipStream_t stream) {
   if (hd.elem != 1 || sl.n_groups == 0) return hipSuccess;
   hipLaunchKernelGGL(attention_reduce, dim3(sl.n_groups * hd.H, (sl.q_block * 16 + 255) / 256), dim3(256), 0, stream, hd,
-                     sl.q_block, sl.reqs, sl.groups, sl.partials, static_cast<uint16_t*>(o));
+                     sl.q_block, sl.reqs, sl.groups, sl.partials, static_cast<uint16_t*>(o), o_half ? 1u : 0u);
   return hipGetLastError();
 }
 
@@ -1537,8 +1608,8 @@ hipError_t launch_scale_q(const void* in, void* out, uint64_t n, hipStream_t str
 hipError_t launch_transpose_weights(const void* w, void* wt, uint32_t rows, uint32_t cols, uint32_t elem,
                                     hipStream_t stream) {
   const dim3 grid((cols + 31) / 32, (rows + 31) / 32), block(32, 8);
-  if (elem == 1)
-    hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, block, 0, stream, static_cast<const uint16_t*>(w),
+  if (elem == 1)  // bf16 in, half precision out
+    hipLaunchKernelGGL(transpose_bf16_to_f16, grid, block, 0, stream, static_cast<const uint16_t*>(w),
                        static_cast<uint16_t*>(wt), rows, cols);
   else
     hipLaunchKernelGGL(transpose_kernel<float>, grid, block, 0, stream, static_cast<const float*>(w),

@@ -175,7 +175,8 @@ hipError_t launch_gemm_front(const HstuDims& hd, uint32_t layer, const void* xn,
 hipError_t launch_gemm_back(const HstuDims& hd, const void* g, const void* w2t, const float* b2,
                             const void* x, void* y, uint32_t N, hipStream_t stream);
 // bf16 models with d = 128 or 256: LayerNorm, projection and epilogue of a layer half in one kernel
-// (front: X -> U, Q*log2(e), K/V pages; back: O, U, X -> Y); weights transposed as for the GEMMs
+// (front: X -> U, Q*log2(e), K/V pages; back: O, U, X -> Y); weights transposed as for the GEMMs.
+// In bf16 models U, O, the normalised matrices and the transposed weights (launch_transpose_weights) are half precision.
 bool layer_halves_fused(const HstuDims& hd);
 hipError_t launch_layer_front_fused(const HstuDims& hd, uint32_t layer, const void* x, const float* ln_g,
                                     const float* ln_b, const void* w1t, const float* b1, void* u, void* q,
@@ -184,11 +185,13 @@ hipError_t launch_layer_front_fused(const HstuDims& hd, uint32_t layer, const vo
 hipError_t launch_layer_back_fused(const HstuDims& hd, const void* o, const void* u, const float* ln_g,
                                    const float* ln_b, const void* w2t, const float* b2, const void* x, void* y,
                                    const StepLists& sl, hipStream_t stream);
+// o_half (bf16 models): the output is written in half precision (the step's own matrix between the attention and the
+// second LayerNorm) instead of bf16 (what a caller of the attention alone gets)
 hipError_t launch_attention(const HstuDims& hd, uint32_t layer, const void* q, const float* pos,
                             const float* time, const KvView& kv, const StepLists& sl,
-                            const int32_t* page_tables, const int64_t* ts, void* o, hipStream_t stream);
+                            const int32_t* page_tables, const int64_t* ts, void* o, bool o_half, hipStream_t stream);
 // adds up the fp32 partials of split attention items (no-op when nothing was split)
-hipError_t launch_attention_reduce(const HstuDims& hd, const StepLists& sl, void* o, hipStream_t stream);
+hipError_t launch_attention_reduce(const HstuDims& hd, const StepLists& sl, void* o, bool o_half, hipStream_t stream);
 // bf16 models: pos and time must be the tables multiplied by log2(e) (launch_scale_bias), and
 // q must already be multiplied by log2(e) (launch_gemm_front stores it that way)
 hipError_t launch_scale_bias(const float* in, float* out, uint64_t n, hipStream_t stream);

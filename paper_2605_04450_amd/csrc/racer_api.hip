@@ -237,7 +237,7 @@ struct racer_pool {
 struct racer_hstu {
   racer_hstu_cfg cfg;
   racer_hstu_weights w;
-  void* w1t = nullptr;  // bf16 models: [L][4d][d], the MFMA kernels want output-major weights
+  void* w1t = nullptr;  // bf16 models: [L][4d][d], the MFMA kernels want output-major weights; half precision copies
   void* w2t = nullptr;  // [L][d][d]
   float* pos_s = nullptr;   // bf16 models: pos and time tables times log2(e), as the attention kernel wants them
   float* time_s = nullptr;
@@ -1142,11 +1142,11 @@ int32_t hstu_step(racer_pool_t* p, racer_hstu_t* m, const racer_hstu_req* reqs, 
       ProfScope t(p, RACER_PROF_ATTENTION, st);
       HIP_TRY(racer::launch_attention(ctx.hd, l, q, bf16 ? m->pos_s : static_cast<const float*>(m->w.pos),
                                       bf16 ? m->time_s : static_cast<const float*>(m->w.time), ctx.kv, sl,
-                                      page_tables, ts, o, st));
+                                      page_tables, ts, o, /*o_half=*/bf16, st));
     }
     if (sl.n_groups) {
       ProfScope t(p, RACER_PROF_ATTN_REDUCE, st);
-      HIP_TRY(racer::launch_attention_reduce(ctx.hd, sl, o, st));
+      HIP_TRY(racer::launch_attention_reduce(ctx.hd, sl, o, /*o_half=*/bf16, st));
     }
     if (fused) {
       ProfScope t(p, RACER_PROF_GEMM_BACK, st);
@@ -1207,11 +1207,11 @@ int32_t hstu_attn_paged(racer_pool_t* p, racer_hstu_t* m, uint32_t layer, const 
     const bool bf16 = m->cfg.elem == RACER_ELEM_BF16;
     HIP_TRY(racer::launch_attention(ctx.hd, layer, q, bf16 ? m->pos_s : static_cast<const float*>(m->w.pos),
                                     bf16 ? m->time_s : static_cast<const float*>(m->w.time), ctx.kv, ctx.sl,
-                                    page_tables, ts, o, stream));
+                                    page_tables, ts, o, /*o_half=*/false, stream));
   }
   if (ctx.sl.n_groups) {
     ProfScope t(p, RACER_PROF_ATTN_REDUCE, stream);
-    HIP_TRY(racer::launch_attention_reduce(ctx.hd, ctx.sl, o, stream));
+    HIP_TRY(racer::launch_attention_reduce(ctx.hd, ctx.sl, o, /*o_half=*/false, stream));
   }
   return RACER_OK;
 }
