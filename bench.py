@@ -86,6 +86,11 @@ CONFIGS = {
                    desc="Refill after growth 0.2 -> 0.5: 64 GiB pool, table 50Mx256 bf16 pinned host, batches of 262144 "
                         "Zipf(0.9) lookups arriving every 4 ms; no refill / one unthrottled refill / 48 MB of refill "
                         "per interval less the interval's live miss bytes"),
+    # What the memory system grants: random row reads out of a 40 GiB region (no cache helps) and a plain copy.
+    # The ceilings against which the gather and the other HBM-bound kernels are read.
+    "hbmceiling": dict(index=7, region_bytes=40 << 30, read_bytes=2 << 30, hbm_ceiling=True,
+                       desc="HBM ceilings: random reads of 128..1024-byte rows out of a 40 GiB region (read only, and "
+                            "written out sequentially), and a sequential device copy of 2 GiB"),
     "tiny": dict(index=0, L=1, d=64, H=2, bf16=False, rows=100_000, pool_bytes=4 << 20, pt=16, alpha=0.5,
                  batch=4, mean_len=256, min_len=256, max_len=256, zipf=1.0, n_time=32, warm_batches=4,
                  desc="Tiny: 1 layer d=64 H=2 fp32, table 100k x 64 fp32, 4 MiB pool, 4 x 256 tokens, KV page 16"),
@@ -664,6 +669,60 @@ def refill_bench(args, c, torch, Hn, B, synth):
         "policies": results}))
 
 
+def hbm_ceiling_bench(args, c, torch, Hn, B, synth):
+    """Rates of racer_hbm_probe (random row reads) and of a plain device copy, HIP events around each launch."""
+    dev = Hn.DEV
+    region = torch.empty(c["region_bytes"], dtype=torch.uint8, device=dev)
+    for piece in region.split(1 << 30):
+        piece.fill_(1)
+    out = torch.empty(c["read_bytes"], dtype=torch.uint8, device=dev)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+
+    def timed(fn):
+        for _ in range(max(args.warmup, 1)):
+            fn()
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(max(args.steps, 1)):
+            ev[0].record()
+            fn()
+            ev[1].record()
+            torch.cuda.synchronize()
+            ms = ev[0].elapsed_time(ev[1])
+            best = ms if best is None else min(best, ms)
+        return best
+
+    rows = []
+    seed = [1]
+    for row_bytes in (128, 256, 512, 1024):
+        n_reads = c["read_bytes"] // row_bytes
+        for write in (False, True):
+            def fn():
+                seed[0] += 1
+                rc = B.racer_hbm_probe(region, row_bytes, n_reads, out if write else None, seed[0])
+                assert rc == B.OK, rc
+            ms = timed(fn)
+            moved = c["read_bytes"] * (2 if write else 1)
+            rows.append({"row_bytes": row_bytes, "written_out": write, "ms": ms, "GBps": moved / ms / 1e6,
+                         "frac_of_hbm_peak": moved / ms / 1e6 / PEAK_HBM_GBS})
+            print("random rows of %4d B, %s: %.3f ms, %.0f GB/s" % (row_bytes, "read + write" if write else "read only", ms,
+                                                                     moved / ms / 1e6), file=sys.stderr, flush=True)
+    src = region[: c["read_bytes"]]
+    ms = timed(lambda: out.copy_(src))
+    copy_gbs = 2 * c["read_bytes"] / ms / 1e6
+    best_read = max(r["GBps"] for r in rows if not r["written_out"])
+    print(json.dumps({
+        "metric": "hbm_random_row_read_GBps", "value": best_read, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": min(r["ms"] for r in rows if not r["written_out"]), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": c["desc"]},
+        "roofline": {"kernel": "random_row_reads", "bound": "hbm", "achieved": best_read, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": best_read / PEAK_HBM_GBS, "traffic": None},
+        "random_rows": rows,
+        "sequential_copy": {"bytes_read_plus_written": 2 * c["read_bytes"], "ms": ms, "GBps": copy_gbs,
+                            "frac_of_hbm_peak": copy_gbs / PEAK_HBM_GBS}}))
+
+
 def one_step(wl, k, B):
     ids = wl["ids_dev"][k % len(wl["ids_dev"])]
     rc = B.emb_lookup(wl["pool"].h, ids, wl["x"], 1, None)
@@ -914,6 +973,9 @@ def main():
         return
     if c.get("append_step"):
         append_step_bench(args, c, torch, Hn, B, synth)
+        return
+    if c.get("hbm_ceiling"):
+        hbm_ceiling_bench(args, c, torch, Hn, B, synth)
         return
     wl = build_workload(c, torch, Hn, B, synth)
     pool = wl["pool"]

@@ -318,6 +318,15 @@ typedef struct {
 int32_t racer_prof_enable(racer_pool_t* pool, int32_t on);
 int32_t racer_prof_read(racer_pool_t* pool, racer_prof* out);
 
+/* ---- racer_hbm_probe: a measurement aid, not part of the serving path.  It reads n_reads rows of row_bytes
+ *      (128, 256, 512 or 1024) bytes, picked by a counter-based hash of (seed, index), out of the bytes at dev_base
+ *      (dev, 16-byte aligned), four rows in flight per lane group, and writes them back to back to dev_out (dev,
+ *      n_reads * row_bytes bytes; NULL: read only).  Timed by the caller, it gives the rate that the memory
+ *      system grants a gather of rows of that size out of a region that no cache holds: the practical ceiling
+ *      against which the embedding gather is read (bench.py --config hbmceiling).  RACER_EINVAL on bad arguments. */
+int32_t racer_hbm_probe(const void* dev_base, uint64_t bytes, uint32_t row_bytes, uint64_t n_reads, void* dev_out,
+                        uint64_t seed, void* stream);
+
 /* text of the last HIP error seen by this library on the calling thread ("" if none) */
 const char* racer_last_error(void);
 

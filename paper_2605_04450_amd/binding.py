@@ -21,7 +21,7 @@ EXPORTS = [
     "pool_num_sets", "pool_slot_of", "kv_seq_reserve", "kv_seq_lookup", "kv_seq_pin", "kv_seq_unpin",
     "kv_seq_release", "emb_lookup", "emb_lookup_noalloc", "emb_refill", "pool_add_table", "emb_lookup_tables", "hstu_model_create", "hstu_model_destroy", "hstu_step",
     "hstu_attn_paged", "racer_last_error", "racer_prof_enable", "racer_prof_read",
-    "alpha_ctl_create", "alpha_ctl_destroy", "alpha_ctl_decide", "alpha_ctl_reward",
+    "alpha_ctl_create", "alpha_ctl_destroy", "alpha_ctl_decide", "alpha_ctl_reward", "racer_hbm_probe",
 ]
 PROF_KINDS = ("emb_gather", "emb_miss", "layernorm", "gemm_front", "attention", "gemm_back", "attn_reduce")
 
@@ -113,6 +113,7 @@ def load():
     L.hstu_model_destroy.argtypes = [vp]
     L.hstu_step.argtypes = [vp, vp, C.POINTER(HstuReq), u32, vp, u64, vp, vp, vp, vp]
     L.hstu_attn_paged.argtypes = [vp, vp, u32, C.POINTER(HstuReq), u32, vp, u64, vp, vp, vp, vp]
+    L.racer_hbm_probe.argtypes = [vp, u64, u32, u64, vp, u64, vp]
     L.racer_prof_enable.argtypes = [vp, i32]
     L.racer_prof_read.argtypes = [vp, C.POINTER(Prof)]
     L.racer_last_error.restype = C.c_char_p
@@ -121,6 +122,12 @@ def load():
             getattr(L, name).restype = i32
     _lib = L
     return L
+
+
+def racer_hbm_probe(region, row_bytes, n_reads, out=None, seed=1, stream=None):
+    """Random row reads out of the device tensor `region` (measurement aid)."""
+    return load().racer_hbm_probe(_dp(region), region.numel() * region.element_size(), row_bytes, n_reads, _dp(out), seed,
+                                  _stream_ptr(stream))
 
 
 def last_error():

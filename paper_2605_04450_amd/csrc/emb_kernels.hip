@@ -826,6 +826,34 @@ __global__ void emb_global_ids(EmbView v, const uint32_t* __restrict__ table_of,
   }
 }
 
+// Measurement aid: what the memory system gives a gather.  Groups of LPR lanes read rows of LPR * 16 bytes picked by
+// a counter-based hash out of [base, base + n_rows rows), ROUNDS rows in flight per group, and (optionally) write
+// them out back to back.  No cache helps when the region is much larger than the caches.
+__device__ __forceinline__ uint64_t splitmix(uint64_t z) {
+  z += 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+template <int LPR, int ROUNDS>
+__global__ __launch_bounds__(256) void random_row_reads(const uint4* __restrict__ base, uint64_t n_rows, uint64_t n_reads,
+                                                        uint4* __restrict__ out, uint64_t seed) {
+  const uint64_t gid = (blockIdx.x * 256ull + threadIdx.x) / LPR, sub = threadIdx.x % LPR;
+  const uint64_t n_groups = gridDim.x * 256ull / LPR;
+  uint4 acc = make_uint4(0, 0, 0, 0);
+  for (uint64_t i = gid * ROUNDS; i + ROUNDS <= n_reads; i += n_groups * ROUNDS) {
+    uint4 v[ROUNDS];
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) v[r] = base[(splitmix(seed + i + r) % n_rows) * LPR + sub];
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+      if (out) out[(i + r) * LPR + sub] = v[r];
+      acc.x ^= v[r].x; acc.y ^= v[r].y; acc.z ^= v[r].z; acc.w ^= v[r].w;
+    }
+  }
+  if (!out && acc.x == 0x12345678u && acc.y == 0x9ABCDEF0u && acc.z == 1u) const_cast<uint4*>(base)[0] = acc;  // keeps the loads alive
+}
+
 __global__ void fill_u32_kernel(uint32_t* p, uint64_t n, uint32_t value) {
   for (uint64_t k = blockIdx.x * static_cast<uint64_t>(blockDim.x) + threadIdx.x; k < n;
        k += static_cast<uint64_t>(gridDim.x) * blockDim.x)
@@ -833,6 +861,21 @@ __global__ void fill_u32_kernel(uint32_t* p, uint64_t n, uint32_t value) {
 }
 
 }  // namespace
+
+hipError_t launch_random_row_reads(const void* base, uint64_t n_rows, uint32_t row_bytes, uint64_t n_reads, void* out,
+                                   uint64_t seed, hipStream_t stream) {
+  const dim3 grid(256 * 8), block(256);
+  const uint4* b = static_cast<const uint4*>(base);
+  uint4* o = static_cast<uint4*>(out);
+  switch (row_bytes) {
+    case 128: hipLaunchKernelGGL((random_row_reads<8, 4>), grid, block, 0, stream, b, n_rows, n_reads, o, seed); break;
+    case 256: hipLaunchKernelGGL((random_row_reads<16, 4>), grid, block, 0, stream, b, n_rows, n_reads, o, seed); break;
+    case 512: hipLaunchKernelGGL((random_row_reads<32, 4>), grid, block, 0, stream, b, n_rows, n_reads, o, seed); break;
+    case 1024: hipLaunchKernelGGL((random_row_reads<64, 2>), grid, block, 0, stream, b, n_rows, n_reads, o, seed); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
 
 hipError_t launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t stream) {
   if (n == 0) return hipSuccess;

@@ -88,6 +88,11 @@ hipError_t launch_emb_shrink(const EmbView& v, uint32_t old_full, uint32_t old_p
 
 hipError_t launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t stream);
 
+// measurement aid: n_reads reads of random rows (128, 256, 512 or 1024 bytes) out of n_rows rows at `base`,
+// written out back to back at `out` unless that is null
+hipError_t launch_random_row_reads(const void* base, uint64_t n_rows, uint32_t row_bytes, uint64_t n_reads, void* out,
+                                   uint64_t seed, hipStream_t stream);
+
 // (table, row) pairs -> global ids (-1 for a table or row that does not exist)
 hipError_t launch_emb_global_ids(const EmbView& v, const uint32_t* table_of, const int64_t* ids, uint32_t n, int64_t* gids,
                                  hipStream_t stream);

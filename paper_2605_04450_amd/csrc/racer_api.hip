@@ -1247,6 +1247,15 @@ double alpha_ctl_reward(double slo_satisfaction, double p99_latency_ms, double s
   return racer::alpha_reward(slo_satisfaction, p99_latency_ms, slo_ms);
 }
 
+int32_t racer_hbm_probe(const void* dev_base, uint64_t bytes, uint32_t row_bytes, uint64_t n_reads, void* dev_out,
+                        uint64_t seed, void* stream_v) {
+  if (!dev_base || n_reads == 0 || (row_bytes != 128 && row_bytes != 256 && row_bytes != 512 && row_bytes != 1024)) return RACER_EINVAL;
+  if (bytes < row_bytes || (reinterpret_cast<uintptr_t>(dev_base) & 15) || (reinterpret_cast<uintptr_t>(dev_out) & 15)) return RACER_EINVAL;
+  HIP_TRY(racer::launch_random_row_reads(dev_base, bytes / row_bytes, row_bytes, n_reads, dev_out, seed,
+                                         static_cast<hipStream_t>(stream_v)));
+  return RACER_OK;
+}
+
 int32_t racer_prof_enable(racer_pool_t* p, int32_t on) {
   if (!p || !p->device) return RACER_EINVAL;
   p->prof_on = on != 0;
