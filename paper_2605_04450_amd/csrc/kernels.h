@@ -107,7 +107,7 @@ struct HstuDims {
 struct ReqDev {  // device copy of one request
   uint32_t prefix_len, new_len;
   uint32_t page_table_off, ts_off, x_off;
-  uint32_t ts_ordered;  // written by the timestamp check: 1 if the request's timestamps never decrease
+  uint32_t ts_ordered;  // 1 from the host, cleared by the timestamp check if the request's timestamps decrease somewhere
 };
 
 struct KvView {
@@ -164,12 +164,13 @@ struct StepLists {
   uint32_t B, N;
 };
 
-// One pass over every request's timestamps: ts_ordered of each request, and the number of requests whose
-// timestamps decrease somewhere added to the kCtrUnorderedTs counter.  The attention kernels take their 32-bit
+// One pass over every request's timestamps (max_seq: the longest request's prefix + new tokens): ts_ordered, which
+// the host has set to 1, is cleared for each request whose timestamps decrease somewhere, and the number of such
+// requests is added to the kCtrUnorderedTs counter.  The attention kernels take their 32-bit
 // relative-time paths only for ordered requests (an unordered one gets the general 64-bit gaps, where a negative gap
 // falls into bucket 0).
-hipError_t launch_check_timestamps(ReqDev* reqs, uint32_t B, const int64_t* ts, unsigned long long* counters,
-                                   hipStream_t stream);
+hipError_t launch_check_timestamps(ReqDev* reqs, uint32_t B, uint32_t max_seq, const int64_t* ts,
+                                   unsigned long long* counters, hipStream_t stream);
 
 hipError_t launch_layernorm(const HstuDims& hd, const void* x, const float* g, const float* b,
                             const void* gate /*nullable: multiply by gate rows*/, void* y, uint32_t N,

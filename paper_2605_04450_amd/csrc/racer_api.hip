@@ -986,7 +986,7 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   uint32_t* hrow = reinterpret_cast<uint32_t*>(hbuf + off_rows);
   for (uint32_t r = 0; r < B; ++r) {
     hr[r] = racer::ReqDev{reqs[r].prefix_len, reqs[r].new_len, static_cast<uint32_t>(reqs[r].page_table_off),
-                          static_cast<uint32_t>(reqs[r].ts_off), static_cast<uint32_t>(reqs[r].x_off), 0 /* set by the check */};
+                          static_cast<uint32_t>(reqs[r].ts_off), static_cast<uint32_t>(reqs[r].x_off), (ts && N) ? 1u : 0u /* cleared by the check */};
     for (uint32_t i = 0; i < reqs[r].new_len; ++i) hrow[reqs[r].x_off + i] = r;
   }
   if (!items.empty()) std::memcpy(hbuf + off_items, items.data(), sizeof(racer::AttnItem) * items.size());
@@ -996,7 +996,11 @@ int32_t prepare_step(racer_pool* p, racer_hstu* m, const racer_hstu_req* reqs, u
   HIP_TRY(hipMemcpyAsync(p->hl_dev, hbuf, total, hipMemcpyHostToDevice, stream));
   if ((rc = p->hstage.mark(which, stream))) return rc;
   // which requests' timestamps never decrease (the attention kernels' 32-bit time paths rely on it)
-  if (ts && N) HIP_TRY(racer::launch_check_timestamps(reinterpret_cast<racer::ReqDev*>(p->hl_dev), B, ts, p->d_counters, stream));
+  if (ts && N) {
+    uint32_t longest = 0;
+    for (uint32_t r = 0; r < B; ++r) longest = std::max(longest, reqs[r].prefix_len + reqs[r].new_len);
+    HIP_TRY(racer::launch_check_timestamps(reinterpret_cast<racer::ReqDev*>(p->hl_dev), B, longest, ts, p->d_counters, stream));
+  }
 
   ctx->esize = esize;
   uint32_t pt_shift = 32;
