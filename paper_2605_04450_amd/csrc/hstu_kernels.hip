@@ -1383,21 +1383,23 @@ __global__ __launch_bounds__(256) void attention_reduce(HstuDims hd, uint32_t q_
 // (eight per thread, all loads independent).  The host sets ts_ordered to 1; the first block that finds a decrease
 // clears it and counts the request.
 constexpr uint32_t kTsChunk = 2048;
-__global__ __launch_bounds__(256) void check_timestamps(ReqDev* __restrict__ reqs, const long long* __restrict__ ts,
+__global__ __launch_bounds__(256) void check_timestamps(ReqDev* __restrict__ reqs, uint32_t B,
+                                                        const long long* __restrict__ ts,
                                                         unsigned long long* __restrict__ counters) {
-  const uint32_t r = blockIdx.y;
-  const uint32_t S = reqs[r].prefix_len + reqs[r].new_len;
-  const uint32_t j0 = blockIdx.x * kTsChunk + 1;
-  if (j0 >= S) return;
-  const long long* t = ts + reqs[r].ts_off;
-  bool bad = false;
+  for (uint32_t r = blockIdx.y; r < B; r += gridDim.y) {  // (the grid's second dimension stops at 65 535)
+    const uint32_t S = reqs[r].prefix_len + reqs[r].new_len;
+    const uint32_t j0 = blockIdx.x * kTsChunk + 1;
+    if (j0 >= S) continue;  // uniform over the block
+    const long long* t = ts + reqs[r].ts_off;
+    bool bad = false;
 #pragma unroll
-  for (uint32_t k = 0; k < kTsChunk / 256; ++k) {
-    const uint32_t j = j0 + k * 256 + threadIdx.x;
-    if (j < S) bad |= t[j] < t[j - 1];
-  }
-  if (__syncthreads_or(bad) && threadIdx.x == 0) {
-    if (atomicExch(&reqs[r].ts_ordered, 0u) == 1u) atomicAdd(&counters[ctr_index(kCtrUnorderedTs)], 1ull);
+    for (uint32_t k = 0; k < kTsChunk / 256; ++k) {
+      const uint32_t j = j0 + k * 256 + threadIdx.x;
+      if (j < S) bad |= t[j] < t[j - 1];
+    }
+    if (__syncthreads_or(bad) && threadIdx.x == 0) {
+      if (atomicExch(&reqs[r].ts_ordered, 0u) == 1u) atomicAdd(&counters[ctr_index(kCtrUnorderedTs)], 1ull);
+    }
   }
 }
 
@@ -1589,9 +1591,8 @@ hipError_t launch_attention_reduce(const HstuDims& hd, const StepLists& sl, void
 hipError_t launch_check_timestamps(ReqDev* reqs, uint32_t B, uint32_t max_seq, const int64_t* ts,
                                    unsigned long long* counters, hipStream_t stream) {
   if (B == 0 || max_seq < 2) return hipSuccess;
-  if (B > 65535) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(check_timestamps, dim3((max_seq - 1 + kTsChunk - 1) / kTsChunk, B), dim3(256), 0, stream, reqs,
-                     reinterpret_cast<const long long*>(ts), counters);
+  hipLaunchKernelGGL(check_timestamps, dim3((max_seq - 1 + kTsChunk - 1) / kTsChunk, B < 65535 ? B : 65535), dim3(256), 0,
+                     stream, reqs, B, reinterpret_cast<const long long*>(ts), counters);
   return hipGetLastError();
 }
 
