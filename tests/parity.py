@@ -18,7 +18,7 @@ FLOOR = 1e-2
 # elementwise one; eight layers 0.017 and 0.8), and an entry at the floor, 1 % of the row's largest,
 # turns that into 100 times the row measure.  The elementwise gate is therefore a guard against
 # regressions (1.5: an entry at the floor may be off by one and a half times the floor), not 2e-2; the
-# measured maxima of every comparison are written to gpurun_out/parity_measured.txt by the test session.
+# measured maxima of every comparison are written to parity_measured.txt by the test session (tests/conftest.py).
 TOL_ROW = {False: 1e-4, True: 2e-2}
 TOL_ELEM = {False: 1e-4, True: 1.5}
 
