@@ -577,7 +577,7 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
     }
   }
   // ---- activations: load, normalise, keep as MFMA operand ----------------------------------
-  __shared__ __attribute__((aligned(16))) float lnp[2][KD];  // LayerNorm scale and shift
+  __shared__ __attribute__((aligned(16))) float lnp[4][KD];  // LayerNorm scale and shift in the first two rows
   for (uint32_t i = tid; i < KD; i += 64 * WPB) {
     lnp[0][i] = a.ln_g[i];
     lnp[1][i] = a.ln_b[i];
@@ -636,7 +636,7 @@ __global__ __attribute__((amdgpu_flat_work_group_size(64 * WPB, 64 * WPB), amdgp
     }
   }
   // The LayerNorm parameters are done with; their LDS space takes this block's slice of the bias (at most
-  // 2 KD columns per block).  Nothing inside the sweep below may read global memory for immediate use: the
+  // 4 KD columns per block).  Nothing inside the sweep below may read global memory for immediate use: the
   // wait for such a load also waits for every store and every weight prefetch issued before it.
   const uint32_t cb0 = blockIdx.y * a.col_blocks_per_split, n_cb = a.col_blocks_per_split;
   float* bias_s = &lnp[0][0];
@@ -1492,7 +1492,9 @@ hipError_t launch_layer_front_fused(const HstuDims& hd, uint32_t layer, const vo
   a.reqs = sl.reqs;
   a.page_tables = page_tables;
   a.row_tiles = sl.row_tiles;
-  constexpr uint32_t kSplit = 2;  // column halves: U|V and Q|K
+  // A block sweeps all 4 d output columns of its rows, so that the rows are read and normalised once; only a launch
+  // with too few row tiles to fill a third of the chip's block slots is cut into the column halves U|V and Q|K.
+  const uint32_t kSplit = sl.n_row_tiles >= 256 ? 1 : 2;
   a.col_blocks_per_split = 4 * hd.d / 32 / kSplit;
   if (a.col_blocks_per_split % 2 != 0) return hipErrorInvalidValue;  // the sweep takes column tiles in pairs
   const dim3 grid(sl.n_row_tiles, kSplit), block(256);
