@@ -774,7 +774,17 @@ def cpu_baseline(c, wl, synth, budget_tokens):
     x = synth.from_bf16_bits(xo) if bf16 else xo
     rc, ref = oracle.hstu_step(cfg, wl["weights"], reqs, pts, kv, x, ts, threads=0)
     dt = time.perf_counter() - t0
+    cpu_model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
     cb = {"value": N / dt, "unit": "tokens/s", "cores": min(threads, len(take)), "kind": "oracle",
+          "wall_s": dt, "cpu_model": cpu_model,
           "sample": "%d requests of the batch in batch order (%d tokens, %.0f causal pairs per token against %.0f for the "
                     "whole batch), EMB lookup + all %d layers, %.1f s, OpenMP over requests (%d threads available)"
                     % (len(take), N, tot / max(N, 1), sum(pairs_of(s) for s in lens) / max(sum(lens), 1), L, dt, threads)}
